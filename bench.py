@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A16 GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+                    [--config c4] [--M 1] [--kernel -1] [--split 0] [--warm] [--table]
+
+A step is one whole GEMM (Eq. 2: every launch w4a16_gemm enqueues for it) on
+seeded synthetic inputs already resident in HBM.  By default consecutive steps
+walk over distinct copies of the weights, scales and zero points totalling
+more than 640 MB, so that no step finds its weights in the 256 MB last-level
+cache ("cold"); --warm reuses one copy and is labelled so.
+
+Prints ONE JSON line on stdout (headline: M=1, K=28672, N=8192).  --table adds
+every configuration of the workload list to the line and writes it under
+gpurun_out/ as well.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 MFMA rate
+COLD_BYTES = 640 * 1024 * 1024
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, warm=False, host=None):
+    """Returns dict with µs per GEMM (HIP events around `steps` back-to-back calls)."""
+    cfg = wl.CONFIGS[name]
+    if host is None:
+        host = wl.make_config(name)
+    Xall, Wp, s, Zp = host
+    X = np.ascontiguousarray(Xall[:M])
+    wbytes = Wp.nbytes + s.nbytes + Zp.nbytes
+    copies = 1 if warm else max(2, -(-COLD_BYTES // wbytes))
+    dX = torch.from_numpy(X).cuda()
+    base = binding.to_device(X, Wp, s, Zp)[1:]
+    sets = [base] + [tuple(t.clone() for t in base) for _ in range(copies - 1)]
+    Y = torch.empty((M, cfg.N), dtype=torch.float16, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def call(i):
+        W_, S_, Z_ = sets[i % copies]
+        binding.gemm_ex(dX, W_, S_, Z_, cfg.group, kernel=kernel, split=split, out=Y, stream=stream)
+
+    for i in range(warmup):
+        call(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(steps):
+        call(warmup + i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / steps
+    nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, cfg.group)
+    flops = 2.0 * M * cfg.K * cfg.N
+    plan = binding.query_plan(M, cfg.N, cfg.K, cfg.group, kernel, split)
+    res = {
+        "config": name, "M": M, "K": cfg.K, "N": cfg.N, "us_per_gemm": us,
+        "algorithmic_bytes": nbytes, "GBps": nbytes / us * 1e-3, "hbm_frac": nbytes / us * 1e-3 / HBM_PEAK_GBS,
+        "TFLOPs": flops / us * 1e-6, "mfma_frac": flops / us * 1e-6 / MFMA_FP16_PEAK_TFLOPS,
+        "cache": "warm (one weight copy, last-level-cache resident)" if warm else "cold (%d weight copies)" % copies,
+        "plan": plan,
+    }
+    return res, Y, (dX, sets[(warmup + steps - 1) % copies])
+
+
+def cpu_baseline(wl, orc, host, M, cfg):
+    """The oracle as it stands, on the host cores, on the same workload."""
+    Xall, Wp, s, Zp = host
+    X = np.ascontiguousarray(Xall[:M])
+    best = None
+    t_all = time.time()
+    reps = 0
+    while reps < 3 or (time.time() - t_all < 6.0 and reps < 10):
+        t = time.time()
+        ref = orc.gemm(X, Wp, s, Zp, cfg.group)
+        dt = time.time() - t
+        best = dt if best is None else min(best, dt)
+        reps += 1
+    return {
+        "value": best * 1e6, "unit": "us/GEMM", "cores": orc.threads(), "kind": "oracle",
+        "sample": "whole %s GEMM (M=%d, K=%d, N=%d), best of %d passes, fp64 scalar C with OpenMP over columns"
+                  % (cfg.name, M, cfg.K, cfg.N, reps),
+    }, ref
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=600)
+    ap.add_argument("--warmup", type=int, default=60)
+    ap.add_argument("--config", default="c4")
+    ap.add_argument("--M", type=int, default=1)
+    ap.add_argument("--kernel", type=int, default=-1)
+    ap.add_argument("--split", type=int, default=0)
+    ap.add_argument("--warm", action="store_true")
+    ap.add_argument("--table", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the host-baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the path is a single-device kernel); --gpus %d is not offered"
+                 % args.gpus)
+
+    import torch
+    from paper_2601_16536_amd import binding, workloads as wl
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    binding.lib()
+    torch.cuda.set_device(0)
+
+    cfg = wl.CONFIGS[args.config]
+    host = wl.make_config(args.config)
+    res, Y, _ = time_gemm(torch, binding, wl, args.config, args.M, args.steps, args.warmup, args.kernel, args.split,
+                          args.warm, host)
+    log("headline:", json.dumps(res))
+
+    from oracle import w4a16_oracle as orc  # host-baseline leg and the parity check of what was timed
+    cpu = None
+    if not args.no_cpu:
+        cpu, ref = cpu_baseline(wl, orc, host, args.M, cfg)
+        out = Y.cpu().numpy().astype(np.float64)
+        ratio = float(np.max(np.abs(out - ref) / (1e-2 * (1 + np.abs(ref)))))
+        log("parity of the timed output vs oracle: err/tol = %.4f" % ratio)
+        if ratio > 1.0:
+            sys.exit("bench.py: timed output fails parity (err/tol = %.3f)" % ratio)
+
+    line = {
+        "metric": "us/GEMM + achieved HBM TB/s (fraction of peak), W4A16 M=1..16, K>>N",
+        "value": res["us_per_gemm"], "unit": "us/GEMM", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["us_per_gemm"] * 1e-3, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 inputs, int4 weights, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "%s: M=%d K=%d N=%d group=%d, W4A16, %s" % (args.config, args.M, cfg.K, cfg.N,
+                                                                          cfg.group, res["cache"]),
+                   "plan": res["plan"]},
+        "achieved_TBps": res["GBps"] * 1e-3, "achieved_TFLOPs": res["TFLOPs"],
+        "roofline": {"bound": "hbm", "achieved": res["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": res["hbm_frac"], "traffic": None},
+        "cpu_baseline": cpu,
+    }
+
+    if args.table:
+        rows = []
+        for name, c in wl.CONFIGS.items():
+            h = host if name == args.config else wl.make_config(name)
+            for M in c.Ms:
+                steps = max(50, min(args.steps, int(2e5 / max(1.0, 1e-6 * c.K * c.N / 16))))
+                r, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), host=h)
+                r2, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), warm=True, host=h)
+                r["us_per_gemm_warm"] = r2["us_per_gemm"]
+                log(json.dumps(r))
+                rows.append(r)
+            del h
+        line["table"] = rows
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
+            json.dump(line, f, indent=1)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

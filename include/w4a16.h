@@ -1,0 +1,140 @@
+/*
+ * w4a16.h -- C ABI of the MI355X (gfx950) W4A16 mixed-precision GEMM library.
+ *
+ * The operation (Section 3, Eq. 2 of the paper):
+ *
+ *     C = A * Dequant(W),     Dequant(W) = s (W - z)
+ *
+ * with A = X in FP16 [M,K], W in INT4 [K,N], partial sums in FP32 and one
+ * final cast to FP16 (Section 3; Algorithm 1 lists the inputs X, W, s, z, the
+ * split factor S and the FP16 output).  Split-K (Algorithm 1, Phases 2 and 3)
+ * is how the library fills the GPU when N is small next to K: K is cut into S
+ * slices on group boundaries, the slices' FP32 partial results go to a
+ * workspace and a second pass adds them in a fixed order and casts to FP16.
+ * Unlike Algorithm 1 (Phase 1) the dequantized weights never travel through
+ * device memory: they are unpacked in registers right after the load.
+ *
+ * Storage (Section 2.2 says only that 4-bit values are packed into wider
+ * integers such as INT32; the layout below is this library's contract):
+ *
+ *   X       FP16   [M, K]        row-major.
+ *   Wpacked uint32 [K/8, N]      row-major (n contiguous).  The unsigned code
+ *                                 (0..15) of k = 8r+i is bits 4i..4i+3 of
+ *                                 Wpacked[r, n].
+ *   scales  FP16   [K/group, N]  row-major; s of (k, n) is scales[k/group, n].
+ *   zeros   uint32 [K/group, N/8] row-major.  The unsigned zero point (0..15,
+ *                                 stored as itself) of n = 8c+j is bits
+ *                                 4j..4j+3 of zeros[g, c].
+ *   Y       FP16   [M, N]        row-major, every element overwritten.
+ *
+ * All data pointers are DEVICE pointers owned by the caller, 16-byte aligned;
+ * the library neither keeps nor frees them.  `stream` is a hipStream_t passed
+ * as void* (NULL = the default stream).  Calls only enqueue work on `stream`;
+ * they never synchronise the device.
+ *
+ * Errors: every function returns a w4a16_status (0 = success).  On any error
+ * nothing is launched and Y is untouched.  Nothing aborts, throws or prints.
+ *
+ * Shapes: M >= 1, N >= 8 with N % 8 == 0, K % group == 0, group a multiple of
+ * 32 (the paper fixes no granularity for s and z; 128 is the tuned case).
+ *
+ * Threads: the library-owned workspace is one per device and is used by every
+ * call on that device, so two calls that overlap in time on one device (on
+ * different streams) race on it unless each passes its own workspace through
+ * w4a16_gemm_ws.  Results are bitwise reproducible for a fixed shape and plan.
+ */
+#ifndef W4A16_H
+#define W4A16_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    W4A16_OK = 0,
+    W4A16_ERR_NULL = 1,        /* a required pointer is NULL                          */
+    W4A16_ERR_SHAPE = 2,       /* M, N or K out of range, or N % 8 / K % 8 != 0        */
+    W4A16_ERR_GROUP = 3,       /* group not a multiple of 32, or K % group != 0        */
+    W4A16_ERR_ALIGN = 4,       /* a data pointer is not 16-byte aligned                */
+    W4A16_ERR_WORKSPACE = 5,   /* caller's workspace too small, or allocation failed   */
+    W4A16_ERR_HIP = 6,         /* the HIP runtime reported an error on launch          */
+    W4A16_ERR_UNSUPPORTED = 7  /* forced kernel / split not valid for this shape       */
+} w4a16_status;
+
+/* Kernel families the scheduler chooses from (Algorithm 1, Phase 2 is the
+ * one multiply phase of the paper; these are its gfx950 forms). */
+typedef enum {
+    W4A16_KERNEL_AUTO = -1,
+    W4A16_KERNEL_DOT2 = 0,      /* lanes along N, packed-FP16 dot products, FP32 accumulate; M <= 4 */
+    W4A16_KERNEL_MFMA_REG = 1,  /* weights unpacked straight into MFMA operand registers; any M    */
+    W4A16_KERNEL_MFMA_LDS = 2   /* dequantized tiles staged in LDS, shared by row tiles; M >= 32   */
+} w4a16_kernel;
+
+/* What the scheduler decided for a shape (Algorithm 1 takes S and the block
+ * sizes as inputs without a rule; here the library derives them). */
+typedef struct {
+    int kernel;            /* a w4a16_kernel value                                        */
+    int split;             /* S: number of K slices (1 = no workspace, Y written directly) */
+    int groups_per_split;  /* quantisation groups per slice (last slice may be shorter)   */
+    int tile_n;            /* output columns per workgroup                                */
+    int tile_m;            /* output rows per workgroup                                   */
+    int workgroups;        /* workgroups of the multiply launch                           */
+    int threads;           /* threads per workgroup                                       */
+    int fused_reduce;      /* 1: last-arriving workgroup reduces; 0: separate reduce pass */
+    size_t workspace_bytes;/* FP32 partials [S, M, N] plus arrival counters               */
+} w4a16_plan;
+
+/*
+ * Y = X * s (W - z)   (Eq. 2), plan chosen by the library's Split-K scheduler,
+ * partial sums in the library-owned workspace of the current device (grown with
+ * hipMalloc on first need, kept until w4a16_shutdown).
+ */
+int w4a16_gemm(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
+               int group, int M, int N, int K, void *Y, void *stream);
+
+/*
+ * The same with the plan forced: `kernel` is a w4a16_kernel (AUTO = choose),
+ * `split` the split factor S (0 = choose; otherwise 1 <= S <= K/group; the
+ * library may lower it so that no slice is empty).  For sweeps and tests.
+ */
+int w4a16_gemm_ex(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
+                  int group, int M, int N, int K, void *Y, void *stream, int kernel, int split);
+
+/*
+ * The same, with the Split-K workspace brought by the caller: `workspace` is
+ * device memory of at least w4a16_workspace_bytes(...) bytes, 256-byte aligned,
+ * ZEROED ONCE by the caller before its first use (the arrival counters in it
+ * return to zero at the end of every call).  Performs no allocation.
+ */
+int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
+                  int group, int M, int N, int K, void *Y, void *stream, int kernel, int split,
+                  void *workspace, size_t workspace_bytes);
+
+/* Upper bound of the workspace any plan for this shape may use (bytes). */
+size_t w4a16_workspace_bytes(int M, int N, int K, int group);
+
+/* The plan w4a16_gemm_ex would run for these arguments (no launch, no GPU call
+ * beyond reading the current device's properties once). */
+int w4a16_query_plan(int M, int N, int K, int group, int kernel, int split, w4a16_plan *out);
+
+/* Second pass alone (Algorithm 1, Phase 3): Y[m,n] = fp16(sum_{i<S} partials[i,m,n]),
+ * i ascending, FP32 adds, round-to-nearest-even cast.  partials: FP32 [S, M, N]. */
+int w4a16_reduce(const float *partials, int S, int M, int N, void *Y, void *stream);
+
+/* Text for a status code (static storage). */
+const char *w4a16_status_string(int status);
+
+/* Text of the last HIP error seen by this thread's failing call ("" if none). */
+const char *w4a16_last_hip_error(void);
+
+/* Frees the library-owned workspaces of all devices.  Call only when no
+ * w4a16 work is in flight. */
+void w4a16_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W4A16_H */

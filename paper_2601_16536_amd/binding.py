@@ -1,0 +1,197 @@
+"""ctypes binding of libw4a16.so: the names of include/w4a16.h, argument
+marshalling only.  torch supplies device memory and the stream handle; every
+step of the computation runs inside the HIP library.  There is no fallback: if
+the library is not built, loading fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libw4a16.so")
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_GROUP, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORTED = range(1, 8)
+KERNEL_AUTO, KERNEL_DOT2, KERNEL_MFMA_REG, KERNEL_MFMA_LDS = -1, 0, 1, 2
+
+EXPORTS = (
+    "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_workspace_bytes", "w4a16_query_plan",
+    "w4a16_reduce", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
+)
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [
+        ("kernel", ctypes.c_int), ("split", ctypes.c_int), ("groups_per_split", ctypes.c_int),
+        ("tile_n", ctypes.c_int), ("tile_m", ctypes.c_int), ("workgroups", ctypes.c_int),
+        ("threads", ctypes.c_int), ("fused_reduce", ctypes.c_int), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+class W4A16Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = "%s: %s" % (where, status_string(status))
+        hip = last_hip_error()
+        if hip:
+            msg += " (%s)" % hip
+        super().__init__(msg)
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_2601_16536_amd.build` "
+                "(there is no CPU or PyTorch fallback)" % LIB_PATH)
+        # torch first: it brings its own HIP runtime (same SONAME as ROCm's), and the
+        # library must bind to that copy -- two HIP runtimes in one process do not
+        # share devices, streams or allocations.
+        import torch  # noqa: F401
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        gemm_args = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp]
+        L.w4a16_gemm.argtypes = gemm_args
+        L.w4a16_gemm_ex.argtypes = gemm_args + [ci, ci]
+        L.w4a16_gemm_ws.argtypes = gemm_args + [ci, ci, vp, sz]
+        L.w4a16_workspace_bytes.argtypes = [ci, ci, ci, ci]
+        L.w4a16_workspace_bytes.restype = sz
+        L.w4a16_query_plan.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(Plan)]
+        L.w4a16_reduce.argtypes = [vp, ci, ci, ci, vp, vp]
+        L.w4a16_status_string.argtypes = [ci]
+        L.w4a16_status_string.restype = ctypes.c_char_p
+        L.w4a16_last_hip_error.argtypes = []
+        L.w4a16_last_hip_error.restype = ctypes.c_char_p
+        L.w4a16_shutdown.argtypes = []
+        L.w4a16_shutdown.restype = None
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().w4a16_status_string(int(status)).decode()
+
+
+def last_hip_error() -> str:
+    return lib().w4a16_last_hip_error().decode()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _check_tensors(X, Wpacked, scales, zeros, group):
+    import torch
+    for name, t, dt in (("X", X, torch.float16), ("Wpacked", Wpacked, torch.int32),
+                        ("scales", scales, torch.float16), ("zeros", zeros, torch.int32)):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != dt:
+            raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (name, dt))
+    M, K = X.shape
+    R, N = Wpacked.shape
+    if R * 8 != K or group < 1 or K % group:
+        raise ValueError("Wpacked %r does not fit X %r / group %d" % (tuple(Wpacked.shape), tuple(X.shape), group))
+    G = K // group
+    if tuple(scales.shape) != (G, N) or N % 8 or tuple(zeros.shape) != (G, N // 8):
+        raise ValueError("scales/zeros shapes do not fit K=%d N=%d group=%d" % (K, N, group))
+    return M, N, K
+
+
+def raw_gemm(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr) -> int:
+    """w4a16_gemm on raw device addresses; returns the status code."""
+    return lib().w4a16_gemm(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr)
+
+
+def raw_gemm_ex(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel, split) -> int:
+    return lib().w4a16_gemm_ex(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel, split)
+
+
+def raw_gemm_ws(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel, split, ws_ptr, ws_bytes) -> int:
+    return lib().w4a16_gemm_ws(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel, split,
+                               ws_ptr, ws_bytes)
+
+
+def gemm(X, Wpacked, scales, zeros, group: int, out=None, stream=None):
+    """Y = X * s (W - z) (Eq. 2).  uint32 storage travels as torch.int32 tensors."""
+    import torch
+    M, N, K = _check_tensors(X, Wpacked, scales, zeros, group)
+    Y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=X.device)
+    rc = raw_gemm(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, M, N, K,
+                  Y.data_ptr(), _stream(stream))
+    if rc:
+        raise W4A16Error(rc, "w4a16_gemm")
+    return Y
+
+
+def gemm_ex(X, Wpacked, scales, zeros, group: int, kernel: int = KERNEL_AUTO, split: int = 0, out=None, stream=None):
+    """As gemm, with the kernel family and the split factor S forced (0 / AUTO = scheduler's choice)."""
+    import torch
+    M, N, K = _check_tensors(X, Wpacked, scales, zeros, group)
+    Y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=X.device)
+    rc = raw_gemm_ex(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, M, N, K,
+                     Y.data_ptr(), _stream(stream), kernel, split)
+    if rc:
+        raise W4A16Error(rc, "w4a16_gemm_ex")
+    return Y
+
+
+def gemm_ws(X, Wpacked, scales, zeros, group: int, workspace, kernel: int = KERNEL_AUTO, split: int = 0, out=None,
+            stream=None):
+    """As gemm_ex, with the caller's zero-initialised workspace tensor (uint8, CUDA)."""
+    import torch
+    M, N, K = _check_tensors(X, Wpacked, scales, zeros, group)
+    Y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=X.device)
+    rc = raw_gemm_ws(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, M, N, K,
+                     Y.data_ptr(), _stream(stream), kernel, split, workspace.data_ptr(),
+                     workspace.numel() * workspace.element_size())
+    if rc:
+        raise W4A16Error(rc, "w4a16_gemm_ws")
+    return Y
+
+
+def workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    return int(lib().w4a16_workspace_bytes(M, N, K, group))
+
+
+def query_plan(M: int, N: int, K: int, group: int, kernel: int = KERNEL_AUTO, split: int = 0) -> dict:
+    p = Plan()
+    rc = lib().w4a16_query_plan(M, N, K, group, kernel, split, ctypes.byref(p))
+    if rc:
+        raise W4A16Error(rc, "w4a16_query_plan")
+    return p.as_dict()
+
+
+def reduce(partials, out=None, stream=None):
+    """Second pass alone (Algorithm 1, Phase 3): fp32 [S, M, N] -> fp16 [M, N]."""
+    import torch
+    if not partials.is_cuda or partials.dtype != torch.float32 or not partials.is_contiguous() or partials.dim() != 3:
+        raise TypeError("partials must be a contiguous CUDA float32 tensor [S, M, N]")
+    S, M, N = partials.shape
+    Y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=partials.device)
+    rc = lib().w4a16_reduce(partials.data_ptr(), S, M, N, Y.data_ptr(), _stream(stream))
+    if rc:
+        raise W4A16Error(rc, "w4a16_reduce")
+    return Y
+
+
+def shutdown() -> None:
+    lib().w4a16_shutdown()
+
+
+def to_device(X, Wp, scales, Zp, device="cuda"):
+    """numpy inputs (float16 / uint32) -> torch tensors on the GPU (uint32 bits as int32)."""
+    import numpy as np
+    import torch
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
+    return (t(X).to(device), t(Wp.view(np.int32)).to(device), t(scales).to(device), t(Zp.view(np.int32)).to(device))

@@ -1,0 +1,272 @@
+// C-ABI layer of the W4A16 GEMM library: argument checks, the Split-K
+// scheduler (Algorithm 1 takes the split factor S and the block sizes as
+// inputs and gives no rule for them; the rule lives here), workspace
+// management and dispatch to the kernel launchers.
+#include "../../include/w4a16.h"
+#include "w4a16_internal.h"
+
+#include <mutex>
+#include <string.h>
+
+namespace {
+
+using namespace w4a16;
+
+constexpr int kMaxDevices = 64;
+constexpr size_t kCounterBytes = 16384;  // 4096 arrival counters in front of the partials
+constexpr int kMaxCounters = (int)(kCounterBytes / sizeof(unsigned));
+
+struct DeviceState {
+    int cus = 0;             // compute units (0 = not read yet)
+    void *ws = nullptr;      // library-owned workspace
+    size_t ws_bytes = 0;
+};
+
+std::mutex g_mutex;
+DeviceState g_dev[kMaxDevices];
+thread_local char t_hip_error[256] = "";
+
+void note_hip_error(hipError_t e)
+{
+    const char *s = hipGetErrorString(e);
+    strncpy(t_hip_error, s ? s : "unknown HIP error", sizeof(t_hip_error) - 1);
+    t_hip_error[sizeof(t_hip_error) - 1] = 0;
+}
+
+// Current device index, or -1 when no GPU is usable (planning still works then,
+// with the MI355X's 256 compute units assumed).
+int current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return -1;
+    }
+    return (dev >= 0 && dev < kMaxDevices) ? dev : -1;
+}
+
+int compute_units(int dev)
+{
+    if (dev < 0) return 256;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (g_dev[dev].cus == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+        }
+        g_dev[dev].cus = cus;
+    }
+    return g_dev[dev].cus;
+}
+
+int check_shape(int group, int M, int N, int K)
+{
+    if (M < 1 || N < 8 || K < 8) return W4A16_ERR_SHAPE;
+    if (N % 8 != 0 || K % 8 != 0) return W4A16_ERR_SHAPE;
+    if (M > 16 * 65535 || (long long)N > (1LL << 30) || (long long)K > (1LL << 30)) return W4A16_ERR_SHAPE;
+    if (group < 32 || group % 32 != 0 || K % group != 0) return W4A16_ERR_GROUP;
+    return W4A16_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- the Split-K scheduler ---------------------------------------------------
+//
+// The multiply launch has tiles = ceil(N / tile_n) * ceil(M / tile_m) independent
+// output tiles.  When that is far below the number of workgroups the GPU can
+// hold (K >> N, the decode case of Section 4.1), K is cut into S slices of whole
+// quantisation groups so that tiles * S workgroups are resident at once, all
+// streaming weights.  S is bounded by the extra traffic of the FP32 partials:
+// 8 S M N bytes written and read against K N / 2 bytes of weights.
+int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4a16_plan *p)
+{
+    const int G = K / group;
+    if (kernel != W4A16_KERNEL_AUTO && kernel != W4A16_KERNEL_MFMA_REG) {
+        // other families are added to this switch as they are built
+        return W4A16_ERR_UNSUPPORTED;
+    }
+    if (split < 0 || split > G) return W4A16_ERR_UNSUPPORTED;
+    p->kernel = W4A16_KERNEL_MFMA_REG;
+    p->tile_n = kTileN;
+    p->tile_m = 16;
+    p->threads = kThreads;
+    const long long tiles = (long long)((N + kTileN - 1) / kTileN) * ((M + 15) / 16);
+    int S = split;
+    if (S == 0) {
+        const long long target = 2LL * cus;  // two workgroups (eight waves) per compute unit
+        S = (int)((target + tiles / 2) / tiles);
+        // partial-sum traffic at most ~1/8 of the weight bytes: 8 S M <= K / 16
+        const long long cap = (long long)K / (128LL * M);
+        if (S > cap) S = (int)cap;
+        if (S < 1) S = 1;
+        if (S > G) S = G;
+    }
+    int gps = (G + S - 1) / S;
+    S = (G + gps - 1) / gps;  // no empty slice
+    p->split = S;
+    p->groups_per_split = gps;
+    p->workgroups = (int)(tiles * S);
+    p->fused_reduce = 0;
+    p->workspace_bytes = S > 1 ? kCounterBytes + (size_t)S * M * N * sizeof(float) : 0;
+    return W4A16_OK;
+}
+
+int ensure_workspace(int dev, size_t bytes, void **out)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState &d = g_dev[dev];
+    if (d.ws_bytes < bytes) {
+        if (d.ws) {
+            // hipFree waits for the device, so work still using the old buffer has drained
+            hipError_t e = hipFree(d.ws);
+            d.ws = nullptr;
+            d.ws_bytes = 0;
+            if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_WORKSPACE; }
+        }
+        size_t want = bytes + bytes / 4;
+        void *ptr = nullptr;
+        hipError_t e = hipMalloc(&ptr, want);
+        if (e != hipSuccess) { note_hip_error(e); (void)hipGetLastError(); return W4A16_ERR_WORKSPACE; }
+        e = hipMemset(ptr, 0, kCounterBytes);
+        if (e != hipSuccess) { note_hip_error(e); (void)hipFree(ptr); return W4A16_ERR_WORKSPACE; }
+        d.ws = ptr;
+        d.ws_bytes = want;
+    }
+    *out = d.ws;
+    return W4A16_OK;
+}
+
+int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *zeros, int group, int M, int N, int K,
+        void *Y, void *stream, int kernel, int split, void *user_ws, size_t user_ws_bytes, bool user_ws_given)
+{
+    t_hip_error[0] = 0;
+    if (!X || !Wp || !scales || !zeros || !Y) return W4A16_ERR_NULL;
+    if (user_ws_given && !user_ws) return W4A16_ERR_NULL;
+    int rc = check_shape(group, M, N, K);
+    if (rc) return rc;
+    if (!aligned16(X) || !aligned16(Wp) || !aligned16(scales) || !aligned16(zeros) || !aligned16(Y)) return W4A16_ERR_ALIGN;
+    if (user_ws_given && (reinterpret_cast<uintptr_t>(user_ws) & 255u)) return W4A16_ERR_ALIGN;
+
+    const int dev = current_device();
+    if (dev < 0) { note_hip_error(hipErrorNoDevice); return W4A16_ERR_HIP; }
+    w4a16_plan plan;
+    rc = make_plan(M, N, K, group, kernel, split, compute_units(dev), &plan);
+    if (rc) return rc;
+
+    void *ws = nullptr;
+    if (plan.workspace_bytes) {
+        if (user_ws_given) {
+            if (user_ws_bytes < plan.workspace_bytes) return W4A16_ERR_WORKSPACE;
+            ws = user_ws;
+        } else {
+            rc = ensure_workspace(dev, plan.workspace_bytes, &ws);
+            if (rc) return rc;
+        }
+    }
+
+    GemmArgs a;
+    a.X = static_cast<const uint16_t *>(X);
+    a.Wp = Wp;
+    a.scales = static_cast<const uint16_t *>(scales);
+    a.Zp = zeros;
+    a.Y = static_cast<uint16_t *>(Y);
+    a.counters = static_cast<unsigned *>(ws);
+    a.partials = ws ? reinterpret_cast<float *>(static_cast<char *>(ws) + kCounterBytes) : nullptr;
+    a.group = group; a.M = M; a.N = N; a.K = K;
+    a.split = plan.split;
+    a.groups_per_split = plan.groups_per_split;
+    a.fused_reduce = plan.fused_reduce;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_mfma_reg(a, st, nullptr);
+    if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+    if (plan.split > 1 && !plan.fused_reduce) {
+        e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);
+        if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+    }
+    return W4A16_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int w4a16_gemm(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int M,
+               int N, int K, void *Y, void *stream)
+{
+    return run(X, Wpacked, scales, zeros, group, M, N, K, Y, stream, W4A16_KERNEL_AUTO, 0, nullptr, 0, false);
+}
+
+int w4a16_gemm_ex(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int M,
+                  int N, int K, void *Y, void *stream, int kernel, int split)
+{
+    return run(X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, nullptr, 0, false);
+}
+
+int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int M,
+                  int N, int K, void *Y, void *stream, int kernel, int split, void *workspace, size_t workspace_bytes)
+{
+    return run(X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, workspace, workspace_bytes, true);
+}
+
+size_t w4a16_workspace_bytes(int M, int N, int K, int group)
+{
+    w4a16_plan p;
+    if (check_shape(group, M, N, K)) return 0;
+    if (make_plan(M, N, K, group, W4A16_KERNEL_AUTO, 0, compute_units(current_device()), &p)) return 0;
+    return p.workspace_bytes ? p.workspace_bytes : 256;
+}
+
+int w4a16_query_plan(int M, int N, int K, int group, int kernel, int split, w4a16_plan *out)
+{
+    if (!out) return W4A16_ERR_NULL;
+    int rc = check_shape(group, M, N, K);
+    if (rc) return rc;
+    return make_plan(M, N, K, group, kernel, split, compute_units(current_device()), out);
+}
+
+int w4a16_reduce(const float *partials, int S, int M, int N, void *Y, void *stream)
+{
+    t_hip_error[0] = 0;
+    if (!partials || !Y) return W4A16_ERR_NULL;
+    if (S < 1 || M < 1 || N < 8 || N % 8 != 0) return W4A16_ERR_SHAPE;
+    if (!aligned16(partials) || !aligned16(Y)) return W4A16_ERR_ALIGN;
+    hipError_t e = launch_reduce(partials, S, M, N, static_cast<uint16_t *>(Y), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+    return W4A16_OK;
+}
+
+const char *w4a16_status_string(int status)
+{
+    switch (status) {
+    case W4A16_OK: return "ok";
+    case W4A16_ERR_NULL: return "null pointer";
+    case W4A16_ERR_SHAPE: return "bad shape (need M >= 1, N % 8 == 0, K % 8 == 0)";
+    case W4A16_ERR_GROUP: return "bad group (need group % 32 == 0 and K % group == 0)";
+    case W4A16_ERR_ALIGN: return "pointer not aligned (16 bytes for data, 256 for a workspace)";
+    case W4A16_ERR_WORKSPACE: return "workspace too small or allocation failed";
+    case W4A16_ERR_HIP: return "HIP runtime error";
+    case W4A16_ERR_UNSUPPORTED: return "forced kernel or split not valid for this shape";
+    default: return "unknown status";
+    }
+}
+
+const char *w4a16_last_hip_error(void) { return t_hip_error; }
+
+void w4a16_shutdown(void)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (int d = 0; d < kMaxDevices; ++d) {
+        if (!g_dev[d].ws) continue;
+        int prev = -1;
+        if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(d) == hipSuccess) {
+            (void)hipFree(g_dev[d].ws);
+            (void)hipSetDevice(prev);
+        }
+        g_dev[d].ws = nullptr;
+        g_dev[d].ws_bytes = 0;
+    }
+}
+
+}  // extern "C"

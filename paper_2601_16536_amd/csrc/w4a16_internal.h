@@ -1,0 +1,36 @@
+// Internal interface between the C-ABI layer (w4a16_api.hip) and the kernel
+// launchers (w4a16_*.hip).  Not installed; callers use include/w4a16.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace w4a16 {
+
+// Arguments every multiply kernel takes (Eq. 2 operands plus the Split-K
+// partition of Algorithm 1, Phase 2).
+struct GemmArgs {
+    const uint16_t *X;        // fp16 [M,K]
+    const uint32_t *Wp;       // [K/8,N]
+    const uint16_t *scales;   // fp16 [K/group,N]
+    const uint32_t *Zp;       // [K/group,N/8]
+    uint16_t *Y;              // fp16 [M,N]
+    float *partials;          // fp32 [S,M,N] (unused when split == 1)
+    unsigned *counters;       // one arrival counter per output tile (fused reduce only)
+    int group, M, N, K;
+    int split;                // S
+    int groups_per_split;
+    int fused_reduce;
+};
+
+constexpr int kTileN = 256;         // columns per workgroup (4 waves x 64)
+constexpr int kThreads = 256;
+constexpr int kLdsBudget = 32768;   // bytes of LDS one workgroup stages X into
+
+// Multiply launchers: enqueue on `stream`, return the launch status.
+hipError_t launch_mfma_reg(const GemmArgs &a, hipStream_t stream, int *workgroups);
+hipError_t launch_dot2(const GemmArgs &a, hipStream_t stream, int *workgroups);
+// Second pass (Algorithm 1, Phase 3).
+hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream);
+
+}  // namespace w4a16

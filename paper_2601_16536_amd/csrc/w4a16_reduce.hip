@@ -1,0 +1,34 @@
+// Second pass of Split-K (Algorithm 1, Phase 3): C = sum_{i<S} C_i element by
+// element in FP32, i ascending, then one round-to-nearest-even cast to FP16.
+#include "w4a16_internal.h"
+
+namespace w4a16 {
+namespace {
+
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+
+// One thread owns four consecutive columns of one row (N % 8 == 0 keeps the
+// 16-byte loads aligned and inside the row).
+__global__ __launch_bounds__(256) void reduce_kernel(const float *__restrict__ partials, int S, size_t MN,
+                                                    uint16_t *__restrict__ Y)
+{
+    const size_t i4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i4 >= MN) return;
+    float4_t acc = *reinterpret_cast<const float4_t *>(partials + i4);
+    for (int s = 1; s < S; ++s) acc += *reinterpret_cast<const float4_t *>(partials + (size_t)s * MN + i4);
+    half4_t h = {(_Float16)acc[0], (_Float16)acc[1], (_Float16)acc[2], (_Float16)acc[3]};
+    *reinterpret_cast<half4_t *>(Y + i4) = h;
+}
+
+}  // namespace
+
+hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream)
+{
+    const size_t MN = (size_t)M * N;
+    const unsigned blocks = (unsigned)((MN / 4 + 255) / 256);
+    hipLaunchKernelGGL(reduce_kernel, dim3(blocks), dim3(256), 0, stream, partials, S, MN, Y);
+    return hipGetLastError();
+}
+
+}  // namespace w4a16

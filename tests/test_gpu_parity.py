@@ -1,0 +1,304 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle.
+
+Bar (floating point): max |Y - ref| <= 1e-2 * (1 + |ref|) against the oracle's
+unrounded binary64 result; bit-exact where the result is an exactly
+representable integer.  Every case prints its name before touching the GPU so
+that a fault names its case.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import w4a16_oracle as orc
+from paper_2601_16536_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2601_16536_amd import binding
+    assert torch.cuda.is_available()
+    binding.lib()  # fails loudly when the HIP library is not built
+    return torch, binding
+
+
+def err_ratio(Y, ref):
+    Y = np.asarray(Y, dtype=np.float64)
+    return float(np.max(np.abs(Y - ref) / (TOL * (1.0 + np.abs(ref)))))
+
+
+def run_gpu(gpu, X, Wp, s, Zp, group, kernel=-1, split=0, poison=True):
+    torch, binding = gpu
+    dX, dW, dS, dZ = binding.to_device(X, Wp, s, Zp)
+    Y = torch.full((X.shape[0], Wp.shape[1]), float("nan"), dtype=torch.float16, device="cuda")
+    binding.gemm_ex(dX, dW, dS, dZ, group, kernel=kernel, split=split, out=Y)
+    torch.cuda.synchronize()
+    out = Y.cpu().numpy()
+    assert not np.isnan(out).any(), "output holds NaN (element not written?)"
+    return out
+
+
+SMALL = [
+    # M, K, N, group
+    (1, 128, 8, 128),
+    (1, 256, 264, 128),
+    (2, 512, 520, 128),
+    (3, 1024, 72, 64),
+    (4, 384, 136, 32),
+    (5, 768, 1032, 128),
+    (8, 2048, 512, 128),
+    (11, 1280, 256, 256),
+    (16, 2048, 776, 128),
+    (17, 1024, 264, 128),
+    (33, 512, 256, 128),
+    (1, 4096, 4104, 128),
+]
+
+
+@pytest.mark.parametrize("M,K,N,group", SMALL)
+def test_small_shapes_every_split(gpu, M, K, N, group):
+    _, binding = gpu
+    X, Wp, s, Zp = wl.make(M, K, N, index=1000 + M + K + N, group=group)
+    ref = orc.gemm(X, Wp, s, Zp, group)
+    G = K // group
+    for split in sorted({0, 1, 2, 3, G}):
+        if split > G:
+            continue
+        say("small", M, K, N, group, "split", split, binding.query_plan(M, N, K, group, -1, split))
+        Y = run_gpu(gpu, X, Wp, s, Zp, group, split=split)
+        r = err_ratio(Y, ref)
+        assert r <= 1.0, (M, K, N, group, split, r)
+
+
+def test_integer_case_bit_exact(gpu):
+    """s = 1, z = 0, X in {-1,0,1}, K = 128: integers below 2048, exactly representable."""
+    rng = np.random.default_rng(21)
+    M, K, N, group = 9, 128, 264, 128
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    Xi = rng.integers(-1, 2, (M, K))
+    X = Xi.astype(np.float16)
+    Wp, Zp = wl.pack_along_k(q), wl.pack_along_n(np.zeros((1, N), np.uint8))
+    s = np.ones((1, N), np.float16)
+    ref = orc.gemm(X, Wp, s, Zp, group)
+    assert np.array_equal(ref, (Xi @ q.astype(np.int64)).astype(np.float64))
+    say("integer exact")
+    Y = run_gpu(gpu, X, Wp, s, Zp, group)
+    assert np.array_equal(Y.astype(np.float64), ref)
+
+
+def test_integer_case_bit_exact_with_zero_points_and_splits(gpu):
+    """Integer scales, random zero points, several groups: still exact in fp32 and fp16."""
+    rng = np.random.default_rng(22)
+    M, K, N, group = 4, 512, 256, 128
+    G = K // group
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    z = rng.integers(0, 16, (G, N), dtype=np.uint8)
+    Xi = np.zeros((M, K), np.int64)
+    for m in range(M):
+        idx = rng.choice(K, size=24, replace=False)
+        Xi[m, idx] = rng.integers(-2, 3, 24)
+    X = Xi.astype(np.float16)
+    s = rng.integers(1, 3, (G, N)).astype(np.float16)
+    Wp, Zp = wl.pack_along_k(q), wl.pack_along_n(z)
+    ref = orc.gemm(X, Wp, s, Zp, group)
+    assert np.abs(ref).max() < 2048 and np.array_equal(ref, np.round(ref))
+    for split in (1, 2, 4):
+        say("integer exact zp", split)
+        Y = run_gpu(gpu, X, Wp, s, Zp, group, split=split)
+        assert np.array_equal(Y.astype(np.float64), ref)
+
+
+def test_one_hot_rows_return_weight_rows(gpu):
+    """X = e_k: Y row is the fp16 rounding of dequantized weight row k (indexing check)."""
+    K, N, group = 256, 264, 128
+    _, Wp, s, Zp = wl.make(1, K, N, index=1234, group=group)
+    ks = [0, 1, 7, 8, 127, 128, 200, 255, 31, 32, 33, 64, 100, 129, 250, 5]
+    X = np.zeros((len(ks), K), np.float16)
+    for i, k in enumerate(ks):
+        X[i, k] = 1.0
+    w = orc.dequant(Wp, s, Zp, group)
+    say("one hot")
+    Y = run_gpu(gpu, X, Wp, s, Zp, group)
+    want = w[ks].astype(np.float16)  # exact fp32 weight, one rounding to fp16
+    assert np.array_equal(Y, want)
+
+
+def test_closed_forms_on_gpu(gpu):
+    """q = z everywhere gives exact zeros; constant code gives s (c - z) rowsum(X)."""
+    rng = np.random.default_rng(23)
+    M, K, N, group = 3, 1024, 520, 128
+    G = K // group
+    z = rng.integers(0, 16, (G, N), dtype=np.uint8)
+    s = rng.uniform(0.001, 0.02, (G, N)).astype(np.float16)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    say("q == z")
+    Y = run_gpu(gpu, X, wl.pack_along_k(np.repeat(z, group, axis=0)), s, wl.pack_along_n(z), group)
+    assert np.array_equal(Y, np.zeros((M, N), np.float16))
+    c, zv, sv = 11, 3, np.float16(0.0123)
+    say("constant code")
+    Y = run_gpu(gpu, X, wl.pack_along_k(np.full((K, N), c, np.uint8)), np.full((G, N), sv, np.float16),
+                wl.pack_along_n(np.full((G, N), zv, np.uint8)), group)
+    want = float(sv) * (c - zv) * X.astype(np.float64).sum(axis=1)
+    assert err_ratio(Y, np.repeat(want[:, None], N, axis=1)) <= 1.0
+    assert (Y == Y[:, :1]).all()  # every column went through the same arithmetic
+
+
+def test_symmetric_int4_as_zero_point_eight(gpu):
+    rng = np.random.default_rng(24)
+    M, K, N, group = 2, 512, 256, 128
+    signed = rng.integers(-8, 8, (K, N))
+    s = rng.uniform(0.001, 0.02, (K // group, N)).astype(np.float16)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    Wp = wl.pack_along_k((signed + 8).astype(np.uint8))
+    Zp = wl.pack_along_n(np.full((K // group, N), 8, np.uint8))
+    ref = orc.gemm(X, Wp, s, Zp, group)
+    say("symmetric")
+    assert err_ratio(run_gpu(gpu, X, Wp, s, Zp, group), ref) <= 1.0
+
+
+def test_deterministic_and_split_invariant(gpu):
+    M, K, N, group = 4, 4096, 1024, 128
+    X, Wp, s, Zp = wl.make(M, K, N, index=77, group=group)
+    ref = orc.gemm(X, Wp, s, Zp, group)
+    outs = {}
+    for split in (0, 1, 4, 32):
+        say("determinism split", split)
+        runs = [run_gpu(gpu, X, Wp, s, Zp, group, split=split) for _ in range(5)]
+        for r in runs[1:]:
+            assert np.array_equal(r.view(np.uint16), runs[0].view(np.uint16))
+        outs[split] = runs[0]
+        assert err_ratio(runs[0], ref) <= 1.0
+    # different S re-associate the same sum: results agree far inside the tolerance
+    for split in (1, 4, 32):
+        d = np.abs(outs[split].astype(np.float64) - outs[0].astype(np.float64))
+        assert np.max(d / (1 + np.abs(ref))) < 2e-3
+
+
+def test_non_default_stream_and_caller_workspace(gpu):
+    torch, binding = gpu
+    M, K, N, group = 2, 2048, 512, 128
+    X, Wp, s, Zp = wl.make(M, K, N, index=78, group=group)
+    ref = orc.gemm(X, Wp, s, Zp, group)
+    dX, dW, dS, dZ = binding.to_device(X, Wp, s, Zp)
+    plan = binding.query_plan(M, N, K, group, -1, 8)
+    ws = torch.zeros(plan["workspace_bytes"] + 256, dtype=torch.uint8, device="cuda")
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + plan["workspace_bytes"]]
+    ws[16384:] = 0xFF  # poison the partials area (NaN bit patterns), counters stay zero
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    say("stream + caller workspace")
+    with torch.cuda.stream(st):
+        for _ in range(3):
+            Y = binding.gemm_ws(dX, dW, dS, dZ, group, ws, split=8, stream=st)
+    st.synchronize()
+    assert err_ratio(Y.cpu().numpy(), ref) <= 1.0
+    with pytest.raises(binding.W4A16Error) as e:
+        binding.gemm_ws(dX, dW, dS, dZ, group, ws[:1024], split=8)
+    assert e.value.status == binding.ERR_WORKSPACE
+
+
+def test_error_codes_leave_output_untouched(gpu):
+    torch, binding = gpu
+    M, K, N, group = 1, 256, 64, 128
+    X, Wp, s, Zp = wl.make(M, K, N, index=79, group=group)
+    dX, dW, dS, dZ = binding.to_device(X, Wp, s, Zp)
+    Y = torch.full((M, N), 7.0, dtype=torch.float16, device="cuda")
+    p = lambda t: t.data_ptr()
+    st = torch.cuda.current_stream().cuda_stream
+    say("error codes")
+    cases = [
+        (binding.ERR_NULL, (0, p(dW), p(dS), p(dZ), group, M, N, K, p(Y), st)),
+        (binding.ERR_NULL, (p(dX), p(dW), p(dS), p(dZ), group, M, N, K, 0, st)),
+        (binding.ERR_SHAPE, (p(dX), p(dW), p(dS), p(dZ), group, 0, N, K, p(Y), st)),
+        (binding.ERR_SHAPE, (p(dX), p(dW), p(dS), p(dZ), group, M, N + 4, K, p(Y), st)),
+        (binding.ERR_SHAPE, (p(dX), p(dW), p(dS), p(dZ), group, M, N, K + 4, p(Y), st)),
+        (binding.ERR_GROUP, (p(dX), p(dW), p(dS), p(dZ), 48, M, N, K, p(Y), st)),
+        (binding.ERR_GROUP, (p(dX), p(dW), p(dS), p(dZ), 96, M, N, K, p(Y), st)),
+        (binding.ERR_ALIGN, (p(dX) + 2, p(dW), p(dS), p(dZ), group, M, N, K, p(Y), st)),
+        (binding.ERR_ALIGN, (p(dX), p(dW), p(dS), p(dZ), group, M, N, K, p(Y) + 8, st)),
+    ]
+    for want, args in cases:
+        assert binding.raw_gemm(*args) == want
+    assert binding.raw_gemm_ex(p(dX), p(dW), p(dS), p(dZ), group, M, N, K, p(Y), st, -1, 3) == binding.ERR_UNSUPPORTED
+    assert binding.raw_gemm_ex(p(dX), p(dW), p(dS), p(dZ), group, M, N, K, p(Y), st, 9, 0) == binding.ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert (Y.cpu().numpy() == 7.0).all()
+    assert binding.raw_gemm(p(dX), p(dW), p(dS), p(dZ), group, M, N, K, p(Y), st) == binding.OK
+    torch.cuda.synchronize()
+    assert err_ratio(Y.cpu().numpy(), orc.gemm(X, Wp, s, Zp, group)) <= 1.0
+
+
+def test_reduce_entry_point(gpu):
+    """Phase 3 alone: fixed-order fp32 sum, one RNE cast."""
+    torch, binding = gpu
+    rng = np.random.default_rng(25)
+    S, M, N = 5, 3, 264
+    P = rng.standard_normal((S, M, N)).astype(np.float32)
+    acc = P[0].copy()
+    for i in range(1, S):
+        acc = (acc + P[i]).astype(np.float32)
+    say("reduce")
+    Y = binding.reduce(torch.from_numpy(P).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy(), acc.astype(np.float16))
+
+
+# ------------------------------------------------------------ full configs ---
+
+def _sample_cols(N, count, seed):
+    rng = np.random.default_rng(seed)
+    cols = set(rng.choice(N, size=count, replace=False).tolist())
+    cols.update([0, 1, 7, 8, 255, 256, N - 257, N - 8, N - 1])  # tile edges
+    return np.array(sorted(cols), dtype=np.int32)
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_baseline_configs_full_size(gpu, name):
+    """Every configuration and every M it lists, in the plan the scheduler picks
+    (the one bench.py times).  M = 1 is checked on every output; larger M on all
+    rows of sampled columns (tile edges included), since each output element is
+    an independent sum the oracle computes one by one."""
+    torch, binding = gpu
+    cfg = wl.CONFIGS[name]
+    Xall, Wp, s, Zp = wl.make_config(name)
+    dW, dS, dZ = [t for t in binding.to_device(Xall, Wp, s, Zp)[1:]]
+    for M in cfg.Ms:
+        X = np.ascontiguousarray(Xall[:M])
+        full = M == 1
+        cols = None if full else _sample_cols(cfg.N, 192, seed=M)
+        ref = orc.gemm(X, Wp, s, Zp, cfg.group, cols=cols)
+        dX = torch.from_numpy(X).cuda()
+        say(name, "M", M, binding.query_plan(M, cfg.N, cfg.K, cfg.group))
+        Y = torch.full((M, cfg.N), float("nan"), dtype=torch.float16, device="cuda")
+        binding.gemm(dX, dW, dS, dZ, cfg.group, out=Y)
+        torch.cuda.synchronize()
+        out = Y.cpu().numpy()
+        assert not np.isnan(out).any()
+        got = out if full else out[:, cols]
+        r = err_ratio(got, ref)
+        print("   err/tol = %.4f" % r, flush=True)
+        assert r <= 1.0, (name, M, r)
+        # properties that hold for every output at any size
+        assert np.isfinite(out).all()
+        x = X.astype(np.float64)
+        gs = x.reshape(M, cfg.K // cfg.group, cfg.group).sum(axis=2)
+        es2 = (0.001 ** 2 + 0.001 * 0.02 + 0.02 ** 2) / 3
+        pred = np.sqrt(es2 * (255.0 / 12.0) * ((x * x).sum(axis=1) + (gs * gs).sum(axis=1)))
+        assert np.all(np.abs(out.astype(np.float64).std(axis=1) / pred - 1) < 0.1)
+        # a forced different split re-associates the same sums: all outputs agree closely
+        S2 = 2 if binding.query_plan(M, cfg.N, cfg.K, cfg.group)["split"] != 2 else 4
+        Y2 = binding.gemm_ex(dX, dW, dS, dZ, cfg.group, split=S2)
+        torch.cuda.synchronize()
+        d = np.abs(Y2.cpu().numpy().astype(np.float64) - out.astype(np.float64))
+        assert np.max(d / (1 + np.abs(out.astype(np.float64)))) < 4e-3
