@@ -9,7 +9,8 @@
  * final cast to FP16 (Section 3; Algorithm 1 lists the inputs X, W, s, z, the
  * split factor S and the FP16 output).  Split-K (Algorithm 1, Phases 2 and 3)
  * is how the library fills the GPU when N is small next to K: K is cut into S
- * slices on group boundaries, the slices' FP32 partial results go to a
+ * slices on group boundaries; slices held by the waves of one workgroup meet in
+ * LDS, slices held by different workgroups put FP32 partial results in a
  * workspace and a second pass adds them in a fixed order and casts to FP16.
  * Unlike Algorithm 1 (Phase 1) the dequantized weights never travel through
  * device memory: they are unpacked in registers right after the load.
@@ -68,23 +69,23 @@ typedef enum {
  * one multiply phase of the paper; these are its gfx950 forms). */
 typedef enum {
     W4A16_KERNEL_AUTO = -1,
-    W4A16_KERNEL_DOT2 = 0,      /* lanes along N, packed-FP16 dot products, FP32 accumulate; M <= 4 */
-    W4A16_KERNEL_MFMA_REG = 1,  /* weights unpacked straight into MFMA operand registers; any M    */
-    W4A16_KERNEL_MFMA_LDS = 2   /* dequantized tiles staged in LDS, shared by row tiles; M >= 32   */
+    W4A16_KERNEL_WAVE_SPLIT = 0, /* M <= 4: narrow column tile per workgroup, its 16 waves split K, LDS reduction */
+    W4A16_KERNEL_MFMA_REG = 1,   /* any M: 256-column tiles, weights unpacked straight into MFMA operand registers */
+    W4A16_KERNEL_MFMA_LDS = 2    /* reserved: dequantized tiles staged in LDS and shared by row tiles (M >= 32)   */
 } w4a16_kernel;
 
 /* What the scheduler decided for a shape (Algorithm 1 takes S and the block
  * sizes as inputs without a rule; here the library derives them). */
 typedef struct {
-    int kernel;            /* a w4a16_kernel value                                        */
-    int split;             /* S: number of K slices (1 = no workspace, Y written directly) */
-    int groups_per_split;  /* quantisation groups per slice (last slice may be shorter)   */
-    int tile_n;            /* output columns per workgroup                                */
-    int tile_m;            /* output rows per workgroup                                   */
-    int workgroups;        /* workgroups of the multiply launch                           */
-    int threads;           /* threads per workgroup                                       */
-    int fused_reduce;      /* 1: last-arriving workgroup reduces; 0: separate reduce pass */
-    size_t workspace_bytes;/* FP32 partials [S, M, N] plus arrival counters               */
+    int kernel;            /* a w4a16_kernel value                                            */
+    int split;             /* S: K slices across workgroups (1 = no workspace, Y written directly) */
+    int groups_per_split;  /* quantisation groups per slice (last slice may be shorter)       */
+    int tile_n;            /* output columns per workgroup                                    */
+    int tile_m;            /* output rows per workgroup                                       */
+    int waves_k;           /* K slices inside a workgroup (waves whose results meet in LDS)   */
+    int workgroups;        /* workgroups of the multiply launch                               */
+    int threads;           /* threads per workgroup                                           */
+    size_t workspace_bytes;/* FP32 partials [S, M, N]; 0 when S == 1                          */
 } w4a16_plan;
 
 /*
@@ -105,15 +106,15 @@ int w4a16_gemm_ex(const void *X, const uint32_t *Wpacked, const void *scales, co
 
 /*
  * The same, with the Split-K workspace brought by the caller: `workspace` is
- * device memory of at least w4a16_workspace_bytes(...) bytes, 256-byte aligned,
- * ZEROED ONCE by the caller before its first use (the arrival counters in it
- * return to zero at the end of every call).  Performs no allocation.
+ * device memory of at least the plan's workspace_bytes (w4a16_query_plan; for
+ * the scheduler's own choice also w4a16_workspace_bytes), 256-byte aligned.
+ * Its contents need no initialisation.  Performs no allocation.
  */
 int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
                   int group, int M, int N, int K, void *Y, void *stream, int kernel, int split,
                   void *workspace, size_t workspace_bytes);
 
-/* Upper bound of the workspace any plan for this shape may use (bytes). */
+/* Workspace bytes of the plan the scheduler itself chooses for this shape (at least 256). */
 size_t w4a16_workspace_bytes(int M, int N, int K, int group);
 
 /* The plan w4a16_gemm_ex would run for these arguments (no launch, no GPU call

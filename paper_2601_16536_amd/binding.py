@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libw4a16.so")
 
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_GROUP, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORTED = range(1, 8)
-KERNEL_AUTO, KERNEL_DOT2, KERNEL_MFMA_REG, KERNEL_MFMA_LDS = -1, 0, 1, 2
+KERNEL_AUTO, KERNEL_WAVE_SPLIT, KERNEL_MFMA_REG, KERNEL_MFMA_LDS = -1, 0, 1, 2
 
 EXPORTS = (
     "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_workspace_bytes", "w4a16_query_plan",
@@ -24,8 +24,8 @@ EXPORTS = (
 class Plan(ctypes.Structure):
     _fields_ = [
         ("kernel", ctypes.c_int), ("split", ctypes.c_int), ("groups_per_split", ctypes.c_int),
-        ("tile_n", ctypes.c_int), ("tile_m", ctypes.c_int), ("workgroups", ctypes.c_int),
-        ("threads", ctypes.c_int), ("fused_reduce", ctypes.c_int), ("workspace_bytes", ctypes.c_size_t),
+        ("tile_n", ctypes.c_int), ("tile_m", ctypes.c_int), ("waves_k", ctypes.c_int), ("workgroups", ctypes.c_int),
+        ("threads", ctypes.c_int), ("workspace_bytes", ctypes.c_size_t),
     ]
 
     def as_dict(self):
@@ -148,7 +148,7 @@ def gemm_ex(X, Wpacked, scales, zeros, group: int, kernel: int = KERNEL_AUTO, sp
 
 def gemm_ws(X, Wpacked, scales, zeros, group: int, workspace, kernel: int = KERNEL_AUTO, split: int = 0, out=None,
             stream=None):
-    """As gemm_ex, with the caller's zero-initialised workspace tensor (uint8, CUDA)."""
+    """As gemm_ex, with the caller's workspace tensor (uint8, CUDA, 256-byte aligned)."""
     import torch
     M, N, K = _check_tensors(X, Wpacked, scales, zeros, group)
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=X.device)

@@ -13,8 +13,6 @@ namespace {
 using namespace w4a16;
 
 constexpr int kMaxDevices = 64;
-constexpr size_t kCounterBytes = 16384;  // 4096 arrival counters in front of the partials
-constexpr int kMaxCounters = (int)(kCounterBytes / sizeof(unsigned));
 
 struct DeviceState {
     int cus = 0;             // compute units (0 = not read yet)
@@ -64,7 +62,7 @@ int check_shape(int group, int M, int N, int K)
 {
     if (M < 1 || N < 8 || K < 8) return W4A16_ERR_SHAPE;
     if (N % 8 != 0 || K % 8 != 0) return W4A16_ERR_SHAPE;
-    if (M > 16 * 65535 || (long long)N > (1LL << 30) || (long long)K > (1LL << 30)) return W4A16_ERR_SHAPE;
+    if (M > 16 * 65535 || N > (1 << 22) || (long long)K > (1LL << 30)) return W4A16_ERR_SHAPE;
     if (group < 32 || group % 32 != 0 || K % group != 0) return W4A16_ERR_GROUP;
     return W4A16_OK;
 }
@@ -73,42 +71,66 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 // ---- the Split-K scheduler ---------------------------------------------------
 //
-// The multiply launch has tiles = ceil(N / tile_n) * ceil(M / tile_m) independent
-// output tiles.  When that is far below the number of workgroups the GPU can
-// hold (K >> N, the decode case of Section 4.1), K is cut into S slices of whole
-// quantisation groups so that tiles * S workgroups are resident at once, all
-// streaming weights.  S is bounded by the extra traffic of the FP32 partials:
-// 8 S M N bytes written and read against K N / 2 bytes of weights.
+// Algorithm 1 takes the split factor S and the block sizes as inputs.  Here:
+//
+// M <= 4 (WAVE_SPLIT): one workgroup of sixteen waves per column tile of 32 or
+//   64 columns; the sixteen waves are sixteen K slices whose partial results
+//   meet in LDS, so this split costs no memory traffic and no second launch.
+//   64-column tiles when they alone give one workgroup per compute unit, else 32.
+//   A split across workgroups (S > 1: fp32 partials in the workspace and the
+//   second pass, about 3.5 us on this GPU) is added only when the column tiles
+//   cover less than half of the compute units, which is where the extra launch
+//   costs less than the idle units.
+// M > 4 (MFMA_REG): 256-column tiles shared by four waves so that X is read
+//   from L2 once per 256 columns; S fills the GPU with about two workgroups per
+//   compute unit, bounded by the partial-sum traffic (8 S M N bytes written and
+//   read against K N / 2 bytes of weights).
 int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4a16_plan *p)
 {
     const int G = K / group;
-    if (kernel != W4A16_KERNEL_AUTO && kernel != W4A16_KERNEL_MFMA_REG) {
-        // other families are added to this switch as they are built
-        return W4A16_ERR_UNSUPPORTED;
-    }
+    if (kernel == W4A16_KERNEL_AUTO) kernel = M <= 4 ? W4A16_KERNEL_WAVE_SPLIT : W4A16_KERNEL_MFMA_REG;
+    if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG) return W4A16_ERR_UNSUPPORTED;
+    if (kernel == W4A16_KERNEL_WAVE_SPLIT && M > 4) return W4A16_ERR_UNSUPPORTED;
     if (split < 0 || split > G) return W4A16_ERR_UNSUPPORTED;
-    p->kernel = W4A16_KERNEL_MFMA_REG;
-    p->tile_n = kTileN;
-    p->tile_m = 16;
-    p->threads = kThreads;
-    const long long tiles = (long long)((N + kTileN - 1) / kTileN) * ((M + 15) / 16);
+    p->kernel = kernel;
+    long long tiles;
     int S = split;
-    if (S == 0) {
-        const long long target = 2LL * cus;  // two workgroups (eight waves) per compute unit
-        S = (int)((target + tiles / 2) / tiles);
-        // partial-sum traffic at most ~1/8 of the weight bytes: 8 S M <= K / 16
-        const long long cap = (long long)K / (128LL * M);
-        if (S > cap) S = (int)cap;
-        if (S < 1) S = 1;
-        if (S > G) S = G;
+    if (kernel == W4A16_KERNEL_WAVE_SPLIT) {
+        p->tile_n = (N + 63) / 64 >= cus ? 64 : 32;
+        p->tile_m = 4;
+        p->waves_k = 16;
+        p->threads = 1024;
+        tiles = (N + p->tile_n - 1) / p->tile_n;
+        if (S == 0) {
+            S = 1;
+            if (2 * tiles < cus) S = (int)((cus + tiles - 1) / tiles);
+            // keep at least one 128-wide unit of K per wave
+            const long long units = (long long)K / 128;
+            while (S > 1 && units / S < p->waves_k) --S;
+        }
+    } else {
+        p->tile_n = kTileN;
+        p->tile_m = 16;
+        p->waves_k = 1;
+        p->threads = kThreads;
+        tiles = (long long)((N + kTileN - 1) / kTileN) * ((M + 15) / 16);
+        if (S == 0) {
+            const long long target = 2LL * cus;  // two workgroups (eight waves) per compute unit
+            S = (int)((target + tiles / 2) / tiles);
+            const long long cap = (long long)K / (128LL * M);  // partial traffic <= ~1/8 of the weight bytes
+            if (S > cap) S = (int)cap;
+        }
     }
+    if (S < 1) S = 1;
+    if (S > G) S = G;
     int gps = (G + S - 1) / S;
+    // slices keep 32-bit buffer offsets: raise S until a slice is below ~2 GiB
+    while ((unsigned long long)gps * (group / 8) * N * 4ull >= 0x7F000000ull && gps > 1) gps = (gps + 1) / 2;
     S = (G + gps - 1) / gps;  // no empty slice
     p->split = S;
     p->groups_per_split = gps;
     p->workgroups = (int)(tiles * S);
-    p->fused_reduce = 0;
-    p->workspace_bytes = S > 1 ? kCounterBytes + (size_t)S * M * N * sizeof(float) : 0;
+    p->workspace_bytes = S > 1 ? (size_t)S * M * N * sizeof(float) : 0;
     return W4A16_OK;
 }
 
@@ -128,8 +150,6 @@ int ensure_workspace(int dev, size_t bytes, void **out)
         void *ptr = nullptr;
         hipError_t e = hipMalloc(&ptr, want);
         if (e != hipSuccess) { note_hip_error(e); (void)hipGetLastError(); return W4A16_ERR_WORKSPACE; }
-        e = hipMemset(ptr, 0, kCounterBytes);
-        if (e != hipSuccess) { note_hip_error(e); (void)hipFree(ptr); return W4A16_ERR_WORKSPACE; }
         d.ws = ptr;
         d.ws_bytes = want;
     }
@@ -171,17 +191,15 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
     a.scales = static_cast<const uint16_t *>(scales);
     a.Zp = zeros;
     a.Y = static_cast<uint16_t *>(Y);
-    a.counters = static_cast<unsigned *>(ws);
-    a.partials = ws ? reinterpret_cast<float *>(static_cast<char *>(ws) + kCounterBytes) : nullptr;
+    a.partials = static_cast<float *>(ws);
     a.group = group; a.M = M; a.N = N; a.K = K;
     a.split = plan.split;
     a.groups_per_split = plan.groups_per_split;
-    a.fused_reduce = plan.fused_reduce;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_mfma_reg(a, st, nullptr);
+    hipError_t e = plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st) : launch_mfma_reg(a, st);
     if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
-    if (plan.split > 1 && !plan.fused_reduce) {
+    if (plan.split > 1) {
         e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);
         if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
     }

@@ -1,0 +1,95 @@
+// Device-side pieces shared by the multiply kernels: operand types, the int4
+// unpack, and the fp32 application of scale and zero point (Eq. 2).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace w4a16 {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
+
+union H2 {
+    uint32_t u;
+    half2_t h;
+};
+union H8 {
+    uint4_t u;
+    half8_t h;
+};
+
+constexpr int kPrefetch = 2;                   // units of weights in flight per wave beyond the one in use
+constexpr uint32_t kOutOfRange = 0x80000000u;  // per-lane buffer offset beyond any slice: the load returns 0, no traffic
+constexpr uint32_t kRawBuffer = 0x00020000u;   // buffer descriptor word 3: raw 32-bit data, no swizzle
+
+// Nibble masks, kept opaque so they stay in scalar registers and each mask is one v_and_b32
+// (as literals they would be re-materialised per use).
+struct Masks {
+    uint32_t lo, hi;  // 0x000F000F, 0x00F000F0
+};
+__device__ __forceinline__ Masks make_masks()
+{
+    Masks m;
+    m.lo = 0x000F000Fu;
+    m.hi = 0x00F000F0u;
+    asm volatile("" : "+s"(m.lo), "+s"(m.hi));
+    return m;
+}
+
+// One 32-bit word holds the codes of k = 8r .. 8r+7 of one column.  A nibble left
+// in place in bits 0-3 of an otherwise zero fp16 IS the subnormal number q 2^-24,
+// in bits 4-7 it is q 2^-20; the MFMA takes subnormal inputs exactly.  So four
+// masks (two of them after a shift by 8) give the lane's eight B-operand halves:
+// k order 0,4 | 1,5 | 2,6 | 3,7 with weights 2^-24, 2^-20, 2^-24, 2^-20.  X is
+// staged in the same k order with the 2^-20 positions divided by 16.
+__device__ __forceinline__ half8_t unpack8(uint32_t w, const Masks &k)
+{
+    const uint32_t w8 = w >> 8;
+    H8 r;
+    r.u = (uint4_t){w & k.lo, w & k.hi, w8 & k.lo, w8 & k.hi};
+    return r.h;
+}
+
+// The eight halves of one packed row of X in unpack order, the bits-4-7 positions scaled by 1/16.
+__device__ __forceinline__ uint4_t permute_x(uint4_t d)
+{
+    const half2_t sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
+    H2 p0, p1, p2, p3;
+    p0.u = (d[0] & 0xFFFFu) | (d[2] << 16);      // x0, x4
+    p1.u = (d[0] >> 16) | (d[2] & 0xFFFF0000u);  // x1, x5
+    p2.u = (d[1] & 0xFFFFu) | (d[3] << 16);      // x2, x6
+    p3.u = (d[1] >> 16) | (d[3] & 0xFFFF0000u);  // x3, x7
+    p1.h = p1.h * sixteenth;
+    p3.h = p3.h * sixteenth;
+    return (uint4_t){p0.u, p1.u, p2.u, p3.u};
+}
+
+__device__ __forceinline__ float sum8(uint4_t d)
+{
+    H8 v;
+    v.u = d;
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += (float)v.h[e];
+    return s;
+}
+
+// With P = 2^-24 sum_k x_k q_k over one unit of k inside a quantisation group
+// (fp32, from the MFMA) and xsum = sum_k x_k, Eq. 2 gives the unit's contribution
+//   sum_k x_k s (q_k - z) = (2^24 s) P - (s z) xsum.
+__device__ __forceinline__ float apply_scale_zero(float tot, float s, float z, float P, float xsum)
+{
+    return __builtin_fmaf(s * 16777216.0f, P, __builtin_fmaf(-s * z, xsum, tot));
+}
+
+__device__ __forceinline__ uint32_t pack_half2(float a, float b)
+{
+    H2 p;
+    p.h = (half2_t){(_Float16)a, (_Float16)b};
+    return p.u;
+}
+
+}  // namespace w4a16

@@ -16,20 +16,18 @@ struct GemmArgs {
     const uint32_t *Zp;       // [K/group,N/8]
     uint16_t *Y;              // fp16 [M,N]
     float *partials;          // fp32 [S,M,N] (unused when split == 1)
-    unsigned *counters;       // one arrival counter per output tile (fused reduce only)
     int group, M, N, K;
     int split;                // S
     int groups_per_split;
-    int fused_reduce;
 };
 
-constexpr int kTileN = 256;         // columns per workgroup (4 waves x 64)
+constexpr int kTileN = 256;         // columns per workgroup of the MFMA_REG family (4 waves x 64)
 constexpr int kThreads = 256;
 constexpr int kLdsBudget = 32768;   // bytes of LDS one workgroup stages X into
 
 // Multiply launchers: enqueue on `stream`, return the launch status.
-hipError_t launch_mfma_reg(const GemmArgs &a, hipStream_t stream, int *workgroups);
-hipError_t launch_dot2(const GemmArgs &a, hipStream_t stream, int *workgroups);
+hipError_t launch_mfma_reg(const GemmArgs &a, hipStream_t stream);
+hipError_t launch_wave_split(const GemmArgs &a, int tile_n, hipStream_t stream);
 // Second pass (Algorithm 1, Phase 3).
 hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream);
 

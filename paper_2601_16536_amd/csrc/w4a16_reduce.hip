@@ -16,7 +16,15 @@ __global__ __launch_bounds__(256) void reduce_kernel(const float *__restrict__ p
     const size_t i4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (i4 >= MN) return;
     float4_t acc = *reinterpret_cast<const float4_t *>(partials + i4);
-    for (int s = 1; s < S; ++s) acc += *reinterpret_cast<const float4_t *>(partials + (size_t)s * MN + i4);
+    int s = 1;
+    for (; s + 8 <= S; s += 8) {  // eight independent loads in flight, added in slice order
+        float4_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = *reinterpret_cast<const float4_t *>(partials + (size_t)(s + e) * MN + i4);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc += v[e];
+    }
+    for (; s < S; ++s) acc += *reinterpret_cast<const float4_t *>(partials + (size_t)s * MN + i4);
     half4_t h = {(_Float16)acc[0], (_Float16)acc[1], (_Float16)acc[2], (_Float16)acc[3]};
     *reinterpret_cast<half4_t *>(Y + i4) = h;
 }
