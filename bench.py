@@ -30,6 +30,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 MFMA rate
 COLD_BYTES = 640 * 1024 * 1024
+# HBM bytes per launch of the headline kernel, from the committed rocprofv3 --pmc summaries
+# (profiles/hbm_traffic_c4_m1.json: FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size).
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def measured_traffic(key):
+    try:
+        with open(TRAFFIC_FILE) as f:
+            return json.load(f).get(key, {}).get("bytes_per_launch")
+    except (OSError, ValueError):
+        return None
 
 
 def log(*a):
@@ -148,7 +159,9 @@ def main():
                    "plan": res["plan"]},
         "achieved_TBps": res["GBps"] * 1e-3, "achieved_TFLOPs": res["TFLOPs"],
         "roofline": {"bound": "hbm", "achieved": res["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": res["hbm_frac"], "traffic": None},
+                     "frac": res["hbm_frac"], "traffic": measured_traffic("%s_M%d" % (args.config, args.M)),
+                     "kernel": "wave_split_kernel" if res["plan"]["kernel"] == 0 else "mfma_reg_kernel",
+                     "algorithmic_bytes_per_launch": res["algorithmic_bytes"]},
         "cpu_baseline": cpu,
     }
 

@@ -79,8 +79,8 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 //   64-column tiles when they alone give one workgroup per compute unit, else 32.
 //   A split across workgroups (S > 1: fp32 partials in the workspace and the
 //   second pass, about 3.5 us on this GPU) is added only when the column tiles
-//   cover less than half of the compute units, which is where the extra launch
-//   costs less than the idle units.
+//   cover at most a quarter of the compute units and the slices stay long, which
+//   is where the extra launch costs less than the idle units.
 // M > 4 (MFMA_REG): 256-column tiles shared by four waves so that X is read
 //   from L2 once per 256 columns; S fills the GPU with about two workgroups per
 //   compute unit, bounded by the partial-sum traffic (8 S M N bytes written and
@@ -102,11 +102,15 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->threads = 1024;
         tiles = (N + p->tile_n - 1) / p->tile_n;
         if (S == 0) {
+            // One launch unless the tiles cover at most a quarter of the compute units AND each
+            // workgroup would still stream at least 128 KiB per slice (below that the second
+            // pass costs more than the idle units).
             S = 1;
-            if (2 * tiles < cus) S = (int)((cus + tiles - 1) / tiles);
-            // keep at least one 128-wide unit of K per wave
-            const long long units = (long long)K / 128;
-            while (S > 1 && units / S < p->waves_k) --S;
+            const long long per_wg = (long long)K * p->tile_n / 2;
+            if (4 * tiles <= cus) {
+                S = (int)(cus / tiles);
+                if (S > per_wg / (128 * 1024)) S = (int)(per_wg / (128 * 1024));
+            }
         }
     } else {
         p->tile_n = kTileN;

@@ -107,20 +107,36 @@ __device__ __forceinline__ void compute_unit(const Unit<STEPS> &u, const uint4_t
 // RPU = rows per unit) into LDS: xs[row][m] = the eight halves of that row in
 // unpack order, positions 1,5,3,7 divided by 16; gs[unit][m] = fp32 sum of the
 // unit's x.  Consecutive threads take consecutive packed rows of one m, so RPU
-// neighbouring lanes hold one unit and a butterfly adds them.
+// neighbouring lanes hold one unit and a butterfly adds them.  Eight loads per
+// thread are in flight before the first is used.
+constexpr int kStageBatch = 8;
+
 template <int MROWS, int RPU>
 __device__ __forceinline__ void stage_x(uint4_t *xs, float *gs, const GemmArgs &a, int m0, int row0, int nrows)
 {
     const int total = nrows * MROWS;
-    for (int idx = threadIdx.x; idx < total; idx += kThreads) {
-        const int m = idx / nrows, kb = idx - m * nrows;
-        uint4_t d = {0u, 0u, 0u, 0u};
-        if (m0 + m < a.M) d = *reinterpret_cast<const uint4_t *>(a.X + (size_t)(m0 + m) * a.K + (size_t)(row0 + kb) * 8);
-        float sum = sum8(d);
+    for (int base = 0; base < total; base += kThreads * kStageBatch) {
+        uint4_t d[kStageBatch];
 #pragma unroll
-        for (int off = 1; off < RPU; off <<= 1) sum += __shfl_xor(sum, off, 64);
-        xs[kb * MROWS + m] = permute_x(d);
-        if ((kb & (RPU - 1)) == 0) gs[(kb / RPU) * MROWS + m] = sum;
+        for (int it = 0; it < kStageBatch; ++it) {
+            const int idx = base + it * kThreads + threadIdx.x;
+            const int m = idx / nrows, kb = idx - m * nrows;
+            d[it] = (uint4_t){0u, 0u, 0u, 0u};
+            if (idx < total && m0 + m < a.M)
+                d[it] = *reinterpret_cast<const uint4_t *>(a.X + (size_t)(m0 + m) * a.K + (size_t)(row0 + kb) * 8);
+        }
+#pragma unroll
+        for (int it = 0; it < kStageBatch; ++it) {
+            const int idx = base + it * kThreads + threadIdx.x;
+            const int m = idx / nrows, kb = idx - m * nrows;
+            float sum = sum8(d[it]);
+#pragma unroll
+            for (int off = 1; off < RPU; off <<= 1) sum += __shfl_xor(sum, off, 64);
+            if (idx < total) {
+                xs[kb * MROWS + m] = permute_x(d[it]);
+                if ((kb & (RPU - 1)) == 0) gs[(kb / RPU) * MROWS + m] = sum;
+            }
+        }
     }
 }
 

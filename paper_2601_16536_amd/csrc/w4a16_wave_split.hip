@@ -16,6 +16,12 @@
 // the fp32 scale / zero-point step are those of w4a16_device.h.  Each wave
 // stages the X values of its own K slice in a private 4 KiB of LDS, so the main
 // loop has no workgroup barrier.
+//
+// Measured and dropped: handing the units of K to the waves through an LDS
+// counter (the waves of a workgroup finish up to 2x apart, but the compute unit's
+// memory throughput, not the slowest wave, sets the time: no gain); more than two
+// units of prefetch per wave (slower: the compute unit's outstanding-miss
+// capacity is already full at two).
 #include "w4a16_device.h"
 #include "w4a16_internal.h"
 
@@ -56,7 +62,7 @@ struct Streams {
 // range-checks against the slice size, is pushed out of range.  Weights are read
 // once: nontemporal.
 template <int STEPS, int VEC>
-__device__ __forceinline__ void load_unit(Unit<STEPS, VEC> &r, const Streams &st, int u, int end, int units_per_group)
+__device__ __forceinline__ void load_unit(Unit<STEPS, VEC> &r, const Streams &st, int u, int end, int group_of_u)
 {
     const bool valid = u < end;
     const uint32_t base = valid ? (uint32_t)u * st.unit_w : 0u;
@@ -67,7 +73,7 @@ __device__ __forceinline__ void load_unit(Unit<STEPS, VEC> &r, const Streams &st
         if constexpr (VEC == 4) r.w[t] = __builtin_amdgcn_raw_buffer_load_b128(st.w, vw, so, 2);
         else r.w[t] = __builtin_amdgcn_raw_buffer_load_b64(st.w, vw, so, 2);
     }
-    const uint32_t g = valid ? (uint32_t)u / (uint32_t)units_per_group : 0u;
+    const uint32_t g = valid ? (uint32_t)group_of_u : 0u;
     if constexpr (VEC == 4) {
         const uint2_t s = __builtin_amdgcn_raw_buffer_load_b64(st.s, vs, g * st.row_s, 0);
         r.sc[0] = s[0];
@@ -110,35 +116,68 @@ __device__ __forceinline__ void compute_unit(const Unit<STEPS, VEC> &u, const ui
 }
 
 // One wave stages X rows 0..MROWS-1, packed rows row0 .. row0+nrows-1 (nrows a
-// multiple of RPU = rows per unit) into its own LDS: xs[row][m] = that row's
-// eight halves in unpack order, gs[unit][m] = fp32 sum of the unit's x.
-template <int MROWS, int RPU>
-__device__ __forceinline__ void stage_x_wave(uint4_t *xs, float *gs, const GemmArgs &a, int lane, int row0, int nrows)
+// multiple of RPU = rows per unit, nrows * MROWS <= 256) into its own LDS:
+// xs[row][m] = that row's eight halves in unpack order, gs[unit][m] = fp32 sum
+// of the unit's x.  Split in two so that all loads are in flight together (and
+// the first weight loads can be issued between the halves).
+constexpr int kStageIters = kWaveLds / 16 / 64;  // 16-byte entries per lane
+
+struct StagedX {
+    uint4_t d[kStageIters];
+};
+
+template <int MROWS>
+__device__ __forceinline__ void stage_x_load(StagedX &r, const GemmArgs &a, int lane, int row0, int nrows)
 {
     const int total = nrows * MROWS;
-    for (int idx = lane; idx < total; idx += 64) {
-        const int m = idx / nrows, kb = idx - m * nrows;
-        uint4_t d = {0u, 0u, 0u, 0u};
-        if (m < a.M) d = *reinterpret_cast<const uint4_t *>(a.X + (size_t)m * a.K + (size_t)(row0 + kb) * 8);
-        float sum = sum8(d);
+    const int nr = nrows > 0 ? nrows : 1;  // a wave with no units stages nothing
 #pragma unroll
-        for (int off = 1; off < RPU; off <<= 1) sum += __shfl_xor(sum, off, 64);
-        xs[kb * MROWS + m] = permute_x(d);
-        if ((kb & (RPU - 1)) == 0) gs[(kb / RPU) * MROWS + m] = sum;
+    for (int it = 0; it < kStageIters; ++it) {
+        const int idx = lane + 64 * it;
+        const int m = idx / nr, kb = idx - m * nr;
+        uint4_t d = {0u, 0u, 0u, 0u};
+        if (idx < total && m < a.M) d = *reinterpret_cast<const uint4_t *>(a.X + (size_t)m * a.K + (size_t)(row0 + kb) * 8);
+        r.d[it] = d;
     }
 }
 
-template <int MROWS, int STEPS, int VEC>
+template <int MROWS, int RPU>
+__device__ __forceinline__ void stage_x_store(const StagedX &r, uint4_t *xs, float *gs, int lane, int nrows)
+{
+    const int total = nrows * MROWS;
+    const int nr = nrows > 0 ? nrows : 1;
+#pragma unroll
+    for (int it = 0; it < kStageIters; ++it) {
+        const int idx = lane + 64 * it;
+        const int m = idx / nr, kb = idx - m * nr;
+        float sum = sum8(r.d[it]);
+#pragma unroll
+        for (int off = 1; off < RPU; off <<= 1) sum += __shfl_xor(sum, off, 64);
+        if (idx < total) {
+            xs[kb * MROWS + m] = permute_x(r.d[it]);
+            if ((kb & (RPU - 1)) == 0) gs[(kb / RPU) * MROWS + m] = sum;
+        }
+    }
+}
+
+template <int MROWS, int STEPS, int VEC, int PF>
 __global__ __launch_bounds__(kWaves * 64) void wave_split_kernel(const GemmArgs a, const int chunk_units)
 {
     constexpr int RPU = 4 * STEPS;     // packed rows per unit
     constexpr int TILE = 16 * VEC;     // columns per workgroup
+    constexpr int RING = PF + 1;
     __shared__ __attribute__((aligned(16))) unsigned char smem[kWaves * kWaveLds];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = lane & 15, g4 = lane >> 4;
-    const int col0 = blockIdx.y * TILE + VEC * j;
+    // Workgroups go round-robin over the 8 XCDs.  Without a split across workgroups,
+    // hand each XCD a contiguous run of column tiles, so that the 128-byte lines of
+    // scales and zero points that neighbouring tiles share are fetched by one L2 only.
+    const int ntiles = gridDim.y;
+    int tile = blockIdx.y;
+    if (gridDim.x == 1 && (ntiles & 7) == 0) tile = (tile & 7) * (ntiles >> 3) + (tile >> 3);
+    const int col0 = tile * TILE + VEC * j;
     const bool ok = col0 < a.N;
     const int mm = j < MROWS ? j : MROWS - 1;
     const int zshift = (col0 & 7) * 4;
@@ -178,22 +217,37 @@ __global__ __launch_bounds__(kWaves * 64) void wave_split_kernel(const GemmArgs 
     uint4_t *xs = reinterpret_cast<uint4_t *>(smem + wave * kWaveLds);
     float *gs = reinterpret_cast<float *>(xs + (size_t)chunk_units * RPU * MROWS);
 
-    Unit<STEPS, VEC> buf[kPrefetch + 1];
+    // X of the first chunk first (mostly L2 hits), then the weight stream.
+    StagedX sx;
+    {
+        const int cn = chunk_units < uend - ubeg ? chunk_units : uend - ubeg;
+        stage_x_load<MROWS>(sx, a, lane, row_base + ubeg * RPU, cn * RPU);
+    }
+    // (lg, lpos): quantisation group of the next unit to load and its position inside the group
+    int lg = ubeg / units_per_group, lpos = ubeg - lg * units_per_group;
+    Unit<STEPS, VEC> buf[RING];
 #pragma unroll
-    for (int p = 0; p < kPrefetch; ++p) load_unit<STEPS, VEC>(buf[p], st, ubeg + p, uend, units_per_group);
+    for (int p = 0; p < PF; ++p) {
+        load_unit<STEPS, VEC>(buf[p], st, ubeg + p, uend, lg);
+        if (++lpos == units_per_group) { lpos = 0; ++lg; }
+    }
 
-    // chunk_units is a multiple of kPrefetch + 1, so buffer p always holds unit ubeg + (multiple of kPrefetch + 1) + p
+    // chunk_units is a multiple of RING, so buffer p always holds unit ubeg + (multiple of RING) + p.
+    // Only this wave touches its LDS and the LDS operations of one wave complete in
+    // order; the fences only keep the compiler from moving them across the staging.
+    // The staging stays outside the unrolled ring so that the loads' wait counts
+    // stay exact (a conditional load inside it makes every wait a full drain).
     for (int cbeg = ubeg; cbeg < uend; cbeg += chunk_units) {
         const int cn = cbeg + chunk_units < uend ? chunk_units : uend - cbeg;
-        // only this wave touches its LDS; LDS operations of one wave complete in order,
-        // the fences keep the compiler from moving them across the staging
+        if (cbeg != ubeg) stage_x_load<MROWS>(sx, a, lane, row_base + cbeg * RPU, cn * RPU);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        stage_x_wave<MROWS, RPU>(xs, gs, a, lane, row_base + cbeg * RPU, cn * RPU);
+        stage_x_store<MROWS, RPU>(sx, xs, gs, lane, cn * RPU);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        for (int u = 0; u < cn; u += kPrefetch + 1) {
+        for (int u = 0; u < cn; u += RING) {
 #pragma unroll
-            for (int p = 0; p <= kPrefetch; ++p) {
-                load_unit<STEPS, VEC>(buf[(p + kPrefetch) % (kPrefetch + 1)], st, cbeg + u + p + kPrefetch, uend, units_per_group);
+            for (int p = 0; p < RING; ++p) {
+                load_unit<STEPS, VEC>(buf[(p + PF) % RING], st, cbeg + u + p + PF, uend, lg);
+                if (++lpos == units_per_group) { lpos = 0; ++lg; }
                 if (u + p < cn)
                     compute_unit<MROWS, STEPS, VEC>(buf[p], xs, gs, (u + p) * RPU, u + p, mm, g4, zshift, masks, tot);
             }
@@ -213,7 +267,7 @@ __global__ __launch_bounds__(kWaves * 64) void wave_split_kernel(const GemmArgs 
     const int t = threadIdx.x;
     if (t < MROWS * TILE) {
         const int m = t / TILE, c = t - m * TILE;
-        const int col = blockIdx.y * TILE + c;
+        const int col = tile * TILE + c;
         if (m < a.M && col < a.N) {
             float acc = red[m * TILE + c];
 #pragma unroll
@@ -236,16 +290,18 @@ hipError_t launch_rows(const GemmArgs &a, hipStream_t stream, dim3 grid)
     const int rpu = steps * 4;
     const int units_per_group = a.group / (32 * steps);
     const int per_unit = rpu * MROWS * 16 + MROWS * 4;  // LDS bytes per unit: X rows plus the unit sums
+    constexpr int PF = kPrefetch;
+    constexpr int ring = PF + 1;
     int chunk_units = kWaveLds / per_unit;
-    chunk_units -= chunk_units % (kPrefetch + 1);
-    if (chunk_units < kPrefetch + 1) return hipErrorInvalidValue;
+    chunk_units -= chunk_units % ring;
+    if (chunk_units < ring) return hipErrorInvalidValue;
     // slice-relative 32-bit buffer offsets must stay below the out-of-range marker
     if ((unsigned long long)a.groups_per_split * units_per_group * rpu * a.N * 4ull >= 0x7F000000ull) return hipErrorInvalidValue;
     const dim3 block(kWaves * 64);
     switch (steps) {
-    case 4: hipLaunchKernelGGL((wave_split_kernel<MROWS, 4, VEC>), grid, block, 0, stream, a, chunk_units); break;
-    case 2: hipLaunchKernelGGL((wave_split_kernel<MROWS, 2, VEC>), grid, block, 0, stream, a, chunk_units); break;
-    default: hipLaunchKernelGGL((wave_split_kernel<MROWS, 1, VEC>), grid, block, 0, stream, a, chunk_units); break;
+    case 4: hipLaunchKernelGGL((wave_split_kernel<MROWS, 4, VEC, PF>), grid, block, 0, stream, a, chunk_units); break;
+    case 2: hipLaunchKernelGGL((wave_split_kernel<MROWS, 2, VEC, PF>), grid, block, 0, stream, a, chunk_units); break;
+    default: hipLaunchKernelGGL((wave_split_kernel<MROWS, 1, VEC, PF>), grid, block, 0, stream, a, chunk_units); break;
     }
     return hipGetLastError();
 }

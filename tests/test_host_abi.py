@@ -1,0 +1,115 @@
+"""Host-side checks that need no GPU: the C-ABI library loads and exports every
+function include/w4a16.h declares, argument checks answer before any GPU call,
+and the Split-K scheduler's plans are well formed."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "w4a16.h")
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2601_16536_amd import binding as b
+    if not os.path.exists(b.LIB_PATH):
+        from paper_2601_16536_amd import build
+        build.build(verbose=False)
+    b.lib()
+    return b
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(w4a16_[a-z_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(binding):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(binding):
+    seen = set()
+    for code in range(0, 8):
+        s = binding.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_argument_checks_need_no_gpu(binding):
+    g = binding.raw_gemm
+    assert g(0, 16, 16, 16, 128, 1, 8, 128, 16, 0) == binding.ERR_NULL
+    assert g(16, 16, 16, 16, 128, 0, 8, 128, 16, 0) == binding.ERR_SHAPE
+    assert g(16, 16, 16, 16, 128, 1, 12, 128, 16, 0) == binding.ERR_SHAPE
+    assert g(16, 16, 16, 16, 128, 1, 8, 132, 16, 0) == binding.ERR_SHAPE
+    assert g(16, 16, 16, 16, 48, 1, 8, 96, 16, 0) == binding.ERR_GROUP
+    assert g(16, 16, 16, 16, 128, 1, 8, 192, 16, 0) == binding.ERR_GROUP
+    assert g(18, 16, 16, 16, 128, 1, 8, 128, 16, 0) == binding.ERR_ALIGN
+    assert binding.raw_gemm_ws(16, 16, 16, 16, 128, 1, 8, 256, 16, 0, -1, 2, 0, 0) == binding.ERR_NULL
+    assert binding.raw_gemm_ws(16, 16, 16, 16, 128, 1, 8, 256, 16, 0, -1, 2, 128, 1 << 20) == binding.ERR_ALIGN
+    with pytest.raises(binding.W4A16Error) as e:
+        binding.query_plan(5, 64, 256, 128, kernel=binding.KERNEL_WAVE_SPLIT)  # that family is for M <= 4
+    assert e.value.status == binding.ERR_UNSUPPORTED
+    with pytest.raises(binding.W4A16Error):
+        binding.query_plan(1, 64, 256, 128, split=3)  # only two groups
+    with pytest.raises(binding.W4A16Error):
+        binding.query_plan(1, 64, 256, 128, kernel=binding.KERNEL_MFMA_LDS)
+
+
+SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336), (16, 4096, 14336), (1, 8192, 28672),
+          (8, 8192, 28672), (32, 8192, 8192), (128, 8192, 8192), (1, 8, 128), (3, 40, 8192), (2, 1024, 28672),
+          (1, 16384, 8192), (7, 264, 1024), (1, 1536, 6144), (1, 7168, 18432)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_plans_are_well_formed(binding, M, N, K):
+    G = K // 128
+    for kernel in (binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG) + ((binding.KERNEL_WAVE_SPLIT,) if M <= 4 else ()):
+        for split in sorted({0, 1, 2, 7, G}):
+            if split > G:
+                continue
+            p = binding.query_plan(M, N, K, 128, kernel, split)
+            S, gps = p["split"], p["groups_per_split"]
+            assert 1 <= S <= G
+            assert S * gps >= G and (S - 1) * gps < G  # slices cover K, none empty
+            if split:
+                assert S <= split
+            assert p["workspace_bytes"] == (S * M * N * 4 if S > 1 else 0)
+            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (0 if M <= 4 else 1))
+            tiles_n = -(-N // p["tile_n"])
+            tiles_m = -(-M // p["tile_m"]) if p["kernel"] == binding.KERNEL_MFMA_REG else 1
+            assert p["workgroups"] == tiles_n * tiles_m * S
+            assert p["threads"] in (256, 1024) and p["waves_k"] in (1, 16)
+    assert binding.workspace_bytes(M, N, K, 128) >= binding.query_plan(M, N, K, 128)["workspace_bytes"]
+
+
+def test_headline_plan_is_one_launch(binding):
+    p = binding.query_plan(1, 8192, 28672, 128)
+    assert p["kernel"] == binding.KERNEL_WAVE_SPLIT and p["split"] == 1 and p["workspace_bytes"] == 0
+    assert p["workgroups"] == 256 and p["waves_k"] == 16
+
+
+def test_product_does_not_touch_the_oracle():
+    """The product path must not import, link or call anything under oracle/."""
+    pkg = os.path.join(ROOT, "paper_2601_16536_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                for needle in ("import oracle", "from oracle", "w4a16_oracle", "oracle/"):
+                    assert needle not in text, (needle, os.path.join(dirpath, f))
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2601_16536_amd" not in text and "libw4a16.so" not in text, f
