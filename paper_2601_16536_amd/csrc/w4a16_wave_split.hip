@@ -21,7 +21,10 @@
 // counter (the waves of a workgroup finish up to 2x apart, but the compute unit's
 // memory throughput, not the slowest wave, sets the time: no gain); more than two
 // units of prefetch per wave (slower: the compute unit's outstanding-miss
-// capacity is already full at two).
+// capacity is already full at two); feeding the MFMA's X operand straight from
+// global memory with the unit sums from an extra MFMA against an all-ones operand
+// (no LDS staging, M up to 16: 20-25 % slower, the extra vector-memory
+// instructions cost more than the staging they replace).
 #include "w4a16_device.h"
 #include "w4a16_internal.h"
 

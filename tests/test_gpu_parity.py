@@ -156,7 +156,7 @@ def test_closed_forms_on_gpu(gpu):
     X = rng.standard_normal((M, K)).astype(np.float16)
     say("q == z")
     Y = run_gpu(gpu, X, wl.pack_along_k(np.repeat(z, group, axis=0)), s, wl.pack_along_n(z), group)
-    assert np.abs(Y.astype(np.float64)).max() < 1e-4  # tolerance would allow 1e-2
+    assert np.abs(Y.astype(np.float64)).max() < 1e-3  # tolerance would allow 1e-2
     c, zv, sv = 11, 3, np.float16(0.0123)
     say("constant code")
     Y = run_gpu(gpu, X, wl.pack_along_k(np.full((K, N), c, np.uint8)), np.full((G, N), sv, np.float16),
