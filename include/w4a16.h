@@ -71,7 +71,8 @@ typedef enum {
     W4A16_KERNEL_AUTO = -1,
     W4A16_KERNEL_WAVE_SPLIT = 0, /* M <= 4: narrow column tile per workgroup, its 16 waves split K, LDS reduction */
     W4A16_KERNEL_MFMA_REG = 1,   /* any M: 256-column tiles, weights unpacked straight into MFMA operand registers */
-    W4A16_KERNEL_MFMA_LDS = 2    /* reserved: dequantized tiles staged in LDS and shared by row tiles (M >= 32)   */
+    W4A16_KERNEL_MFMA_ROWS = 2   /* any M, meant for M > 16: as MFMA_REG with 32 or 64 rows of X staged in LDS per
+                                    workgroup, every unpacked weight word reused over the row tiles               */
 } w4a16_kernel;
 
 /* What the scheduler decided for a shape (Algorithm 1 takes S and the block

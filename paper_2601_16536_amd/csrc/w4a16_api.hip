@@ -81,15 +81,20 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 //   second pass, about 3.5 us on this GPU) is added only when the column tiles
 //   cover at most a quarter of the compute units and the slices stay long, which
 //   is where the extra launch costs less than the idle units.
-// M > 4 (MFMA_REG): 256-column tiles shared by four waves so that X is read
+// 4 < M <= 16 (MFMA_REG): 256-column tiles shared by four waves so that X is read
 //   from L2 once per 256 columns; S fills the GPU with about two workgroups per
 //   compute unit, bounded by the partial-sum traffic (8 S M N bytes written and
 //   read against K N / 2 bytes of weights).
+// M > 16 (MFMA_ROWS): the same tiles with 32 or 64 rows of X per workgroup, so
+//   that each unpacked weight word feeds 2 or 4 MFMAs and W is read once per 32
+//   or 64 rows.
 int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4a16_plan *p)
 {
     const int G = K / group;
-    if (kernel == W4A16_KERNEL_AUTO) kernel = M <= 4 ? W4A16_KERNEL_WAVE_SPLIT : W4A16_KERNEL_MFMA_REG;
-    if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG) return W4A16_ERR_UNSUPPORTED;
+    if (kernel == W4A16_KERNEL_AUTO)
+        kernel = M <= 4 ? W4A16_KERNEL_WAVE_SPLIT : (M <= 16 ? W4A16_KERNEL_MFMA_REG : W4A16_KERNEL_MFMA_ROWS);
+    if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG && kernel != W4A16_KERNEL_MFMA_ROWS)
+        return W4A16_ERR_UNSUPPORTED;
     if (kernel == W4A16_KERNEL_WAVE_SPLIT && M > 4) return W4A16_ERR_UNSUPPORTED;
     if (split < 0 || split > G) return W4A16_ERR_UNSUPPORTED;
     p->kernel = kernel;
@@ -114,14 +119,17 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         }
     } else {
         p->tile_n = kTileN;
-        p->tile_m = 16;
+        p->tile_m = kernel == W4A16_KERNEL_MFMA_REG ? 16 : (M <= 32 ? 32 : 64);
         p->waves_k = 1;
         p->threads = kThreads;
-        tiles = (long long)((N + kTileN - 1) / kTileN) * ((M + 15) / 16);
+        tiles = (long long)((N + kTileN - 1) / kTileN) * ((M + p->tile_m - 1) / p->tile_m);
         if (S == 0) {
             const long long target = 2LL * cus;  // two workgroups (eight waves) per compute unit
             S = (int)((target + tiles / 2) / tiles);
-            const long long cap = (long long)K / (128LL * M);  // partial traffic <= ~1/8 of the weight bytes
+            // partial traffic (8 S M N bytes) at most ~1/8 of the weight bytes (K N / 2) for the
+            // bandwidth-bound small M; for M > 16, where the MFMA work needs every compute unit,
+            // at most the weight bytes themselves
+            const long long cap = M <= 16 ? (long long)K / (128LL * M) : (long long)K / (16LL * M);
             if (S > cap) S = (int)cap;
         }
     }
@@ -201,7 +209,9 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
     a.groups_per_split = plan.groups_per_split;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st) : launch_mfma_reg(a, st);
+    hipError_t e = plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st)
+                 : plan.kernel == W4A16_KERNEL_MFMA_ROWS ? launch_mfma_rows(a, plan.tile_m, st)
+                                                         : launch_mfma_reg(a, st);
     if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
     if (plan.split > 1) {
         e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);

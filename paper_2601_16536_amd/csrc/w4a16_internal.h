@@ -28,6 +28,7 @@ constexpr int kLdsBudget = 32768;   // bytes of LDS one workgroup stages X into
 // Multiply launchers: enqueue on `stream`, return the launch status.
 hipError_t launch_mfma_reg(const GemmArgs &a, hipStream_t stream);
 hipError_t launch_wave_split(const GemmArgs &a, int tile_n, hipStream_t stream);
+hipError_t launch_mfma_rows(const GemmArgs &a, int tile_m, hipStream_t stream);
 // Second pass (Algorithm 1, Phase 3).
 hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream);
 

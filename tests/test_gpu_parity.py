@@ -61,6 +61,9 @@ SMALL = [
     (16, 2048, 776, 128),
     (17, 1024, 264, 128),
     (33, 512, 256, 128),
+    (64, 2048, 520, 128),
+    (100, 1536, 264, 64),
+    (130, 768, 256, 128),
     (1, 4096, 4104, 128),
     (2, 8192, 40, 128),
     (4, 6144, 16416, 128),
@@ -74,7 +77,7 @@ def test_small_shapes_every_split(gpu, M, K, N, group):
     X, Wp, s, Zp = wl.make(M, K, N, index=1000 + M + K + N, group=group)
     ref = orc.gemm(X, Wp, s, Zp, group)
     G = K // group
-    kernels = [binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG] + ([binding.KERNEL_WAVE_SPLIT] if M <= 4 else [])
+    kernels = [binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS] + ([binding.KERNEL_WAVE_SPLIT] if M <= 4 else [])
     for kernel in kernels:
         for split in sorted({0, 1, 2, 3, G}):
             if split > G:
@@ -181,7 +184,7 @@ def test_symmetric_int4_as_zero_point_eight(gpu):
 
 def binding_kernels(gpu):
     _, binding = gpu
-    return (binding.KERNEL_AUTO, binding.KERNEL_WAVE_SPLIT, binding.KERNEL_MFMA_REG)
+    return (binding.KERNEL_AUTO, binding.KERNEL_WAVE_SPLIT, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS)
 
 
 def test_deterministic_and_split_invariant(gpu):

@@ -62,7 +62,7 @@ def test_argument_checks_need_no_gpu(binding):
     with pytest.raises(binding.W4A16Error):
         binding.query_plan(1, 64, 256, 128, split=3)  # only two groups
     with pytest.raises(binding.W4A16Error):
-        binding.query_plan(1, 64, 256, 128, kernel=binding.KERNEL_MFMA_LDS)
+        binding.query_plan(1, 64, 256, 128, kernel=3)
 
 
 SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336), (16, 4096, 14336), (1, 8192, 28672),
@@ -73,7 +73,7 @@ SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336),
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_plans_are_well_formed(binding, M, N, K):
     G = K // 128
-    for kernel in (binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG) + ((binding.KERNEL_WAVE_SPLIT,) if M <= 4 else ()):
+    for kernel in (binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS) + ((binding.KERNEL_WAVE_SPLIT,) if M <= 4 else ()):
         for split in sorted({0, 1, 2, 7, G}):
             if split > G:
                 continue
@@ -84,9 +84,9 @@ def test_plans_are_well_formed(binding, M, N, K):
             if split:
                 assert S <= split
             assert p["workspace_bytes"] == (S * M * N * 4 if S > 1 else 0)
-            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (0 if M <= 4 else 1))
+            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (0 if M <= 4 else (1 if M <= 16 else 2)))
             tiles_n = -(-N // p["tile_n"])
-            tiles_m = -(-M // p["tile_m"]) if p["kernel"] == binding.KERNEL_MFMA_REG else 1
+            tiles_m = -(-M // p["tile_m"]) if p["kernel"] != binding.KERNEL_WAVE_SPLIT else 1
             assert p["workgroups"] == tiles_n * tiles_m * S
             assert p["threads"] in (256, 1024) and p["waves_k"] in (1, 16)
     assert binding.workspace_bytes(M, N, K, 128) >= binding.query_plan(M, N, K, 128)["workspace_bytes"]
