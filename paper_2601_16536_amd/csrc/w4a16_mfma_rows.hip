@@ -61,18 +61,28 @@ __device__ __forceinline__ void compute_unit(const Unit<STEPS> &u, const uint4_t
     for (int r = 0; r < RT; ++r)
 #pragma unroll
         for (int c = 0; c < 4; ++c) part[r][c] = (float4_t){0.f, 0.f, 0.f, 0.f};
+    // A fragments for step t + 1 are read from LDS before the MFMAs of step t are issued,
+    // so that a wave alone on its SIMD does not sit out the LDS latency sixteen times per unit.
+    H8 x[2][RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) x[0][r].u = xs[(lrow0 + g4) * MROWS + 16 * r + j];
 #pragma unroll
     for (int t = 0; t < STEPS; ++t) {
+        if (t + 1 < STEPS) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r) x[(t + 1) & 1][r].u = xs[(lrow0 + 4 * (t + 1) + g4) * MROWS + 16 * r + j];
+        }
         half8_t b[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) b[c] = unpack8(u.w[t][c], k);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r = 0; r < RT; ++r) {
-            H8 x;
-            x.u = xs[(lrow0 + 4 * t + g4) * MROWS + 16 * r + j];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) part[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, b[c], part[r][c], 0, 0, 0);
+            for (int c = 0; c < 4; ++c)
+                part[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x[t & 1][r].h, b[c], part[r][c], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
     H2 s01, s23;
     s01.u = u.sc[0];
