@@ -47,8 +47,10 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, warm=False, host=None):
-    """Returns dict with µs per GEMM (HIP events around `steps` back-to-back calls)."""
+def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, warm=False, host=None, graph=True,
+              replays=3):
+    """Returns dict with µs per GEMM: HIP events around `steps` back-to-back GEMMs (one replay of a HIP graph
+    that holds them, best of `replays`; graph=False times the eager Python loop instead)."""
     cfg = wl.CONFIGS[name]
     if host is None:
         host = wl.make_config(name)
@@ -64,18 +66,37 @@ def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, wa
 
     def call(i):
         W_, S_, Z_ = sets[i % copies]
-        binding.gemm_ex(dX, W_, S_, Z_, cfg.group, kernel=kernel, split=split, out=Y, stream=stream)
+        binding.gemm_ex(dX, W_, S_, Z_, cfg.group, kernel=kernel, split=split, out=Y, stream=torch.cuda.current_stream())
 
     for i in range(warmup):
         call(i)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for i in range(steps):
-        call(warmup + i)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / steps
+    if graph:
+        # The K steps are recorded once into a HIP graph (kernel launches only) and replayed: the GPU then
+        # runs them back to back, and the Python cost of a call (several us) stays out of the measurement.
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(steps):
+                call(warmup + i)
+        g.replay()  # untimed: first replay of a new graph
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(replays):
+            e0.record(stream)
+            g.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        us = best * 1e3 / steps
+    else:
+        e0.record(stream)
+        for i in range(steps):
+            call(warmup + i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / steps
     nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, cfg.group)
     flops = 2.0 * M * cfg.K * cfg.N
     plan = binding.query_plan(M, cfg.N, cfg.K, cfg.group, kernel, split)

@@ -10,8 +10,10 @@
  * split factor S and the FP16 output).  Split-K (Algorithm 1, Phases 2 and 3)
  * is how the library fills the GPU when N is small next to K: K is cut into S
  * slices on group boundaries; slices held by the waves of one workgroup meet in
- * LDS, slices held by different workgroups put FP32 partial results in a
- * workspace and a second pass adds them in a fixed order and casts to FP16.
+ * LDS; slices held by different workgroups either add their sums into a 64-bit
+ * fixed-point accumulator whose last arriver casts to FP16 (M <= 4), or put FP32
+ * partial results in a workspace that a second pass adds in a fixed order and
+ * casts to FP16.
  * Unlike Algorithm 1 (Phase 1) the dequantized weights never travel through
  * device memory: they are unpacked in registers right after the load.
  *
@@ -71,8 +73,11 @@ typedef enum {
     W4A16_KERNEL_AUTO = -1,
     W4A16_KERNEL_WAVE_SPLIT = 0, /* M <= 4: narrow column tile per workgroup, its 16 waves split K, LDS reduction */
     W4A16_KERNEL_MFMA_REG = 1,   /* any M: 256-column tiles, weights unpacked straight into MFMA operand registers */
-    W4A16_KERNEL_MFMA_ROWS = 2   /* any M, meant for M > 16: as MFMA_REG with 32 or 64 rows of X staged in LDS per
+    W4A16_KERNEL_MFMA_ROWS = 2,  /* any M, meant for M > 16: as MFMA_REG with 32 or 64 rows of X staged in LDS per
                                     workgroup, every unpacked weight word reused over the row tiles               */
+    W4A16_KERNEL_STRIPE = 3      /* M <= 4: 256-column stripe x K slice per workgroup, its waves own contiguous runs
+                                    of the slice (LDS reduction); slices of different workgroups meet in a 64-bit
+                                    fixed-point accumulator by one atomic add each, no second launch              */
 } w4a16_kernel;
 
 /* What the scheduler decided for a shape (Algorithm 1 takes S and the block
@@ -86,7 +91,7 @@ typedef struct {
     int waves_k;           /* K slices inside a workgroup (waves whose results meet in LDS)   */
     int workgroups;        /* workgroups of the multiply launch                               */
     int threads;           /* threads per workgroup                                           */
-    size_t workspace_bytes;/* FP32 partials [S, M, N]; 0 when S == 1                          */
+    size_t workspace_bytes;/* FP32 partials [S, M, N] (STRIPE: 64-bit sums [M, N]); 0 when S == 1 */
 } w4a16_plan;
 
 /*
@@ -109,7 +114,8 @@ int w4a16_gemm_ex(const void *X, const uint32_t *Wpacked, const void *scales, co
  * The same, with the Split-K workspace brought by the caller: `workspace` is
  * device memory of at least the plan's workspace_bytes (w4a16_query_plan; for
  * the scheduler's own choice also w4a16_workspace_bytes), 256-byte aligned.
- * Its contents need no initialisation.  Performs no allocation.
+ * Its contents need no initialisation (for a STRIPE plan the library clears it
+ * with one small extra launch first).  Performs no allocation.
  */
 int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
                   int group, int M, int N, int K, void *Y, void *stream, int kernel, int split,

@@ -5,6 +5,7 @@
 #include "../../include/w4a16.h"
 #include "w4a16_internal.h"
 
+#include <cstdlib>
 #include <mutex>
 #include <string.h>
 
@@ -16,8 +17,10 @@ constexpr int kMaxDevices = 64;
 
 struct DeviceState {
     int cus = 0;             // compute units (0 = not read yet)
-    void *ws = nullptr;      // library-owned workspace
+    void *ws = nullptr;      // library-owned workspace (fp32 partials of the two-pass plans)
     size_t ws_bytes = 0;
+    void *acc = nullptr;     // library-owned fixed-point accumulator of the STRIPE family: all zero between calls
+    size_t acc_bytes = 0;
 };
 
 std::mutex g_mutex;
@@ -92,14 +95,47 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
 {
     const int G = K / group;
     if (kernel == W4A16_KERNEL_AUTO)
-        kernel = M <= 4 ? W4A16_KERNEL_WAVE_SPLIT : (M <= 16 ? W4A16_KERNEL_MFMA_REG : W4A16_KERNEL_MFMA_ROWS);
-    if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG && kernel != W4A16_KERNEL_MFMA_ROWS)
+        kernel = M <= 4 ? W4A16_KERNEL_STRIPE : (M <= 16 ? W4A16_KERNEL_MFMA_REG : W4A16_KERNEL_MFMA_ROWS);
+    if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG && kernel != W4A16_KERNEL_MFMA_ROWS &&
+        kernel != W4A16_KERNEL_STRIPE)
         return W4A16_ERR_UNSUPPORTED;
-    if (kernel == W4A16_KERNEL_WAVE_SPLIT && M > 4) return W4A16_ERR_UNSUPPORTED;
+    if ((kernel == W4A16_KERNEL_WAVE_SPLIT || kernel == W4A16_KERNEL_STRIPE) && M > 4) return W4A16_ERR_UNSUPPORTED;
     if (split < 0 || split > G) return W4A16_ERR_UNSUPPORTED;
     p->kernel = kernel;
     long long tiles;
     int S = split;
+    if (kernel == W4A16_KERNEL_STRIPE) {
+        p->tile_n = 256;
+        p->tile_m = 4;
+        tiles = (N + 255) / 256;
+        if (S == 0) S = (int)((cus + tiles / 2) / tiles);  // one workgroup per compute unit
+        if (S > 255) S = 255;                               // arrival count of the accumulator
+        if (S < 1) S = 1;
+        if (S > G) S = G;
+        int gps = (G + S - 1) / S;
+        // the slice's X rows must fit the workgroup's LDS and its weights a 31-bit buffer: shorten the slice if not
+        while (gps > 1 && (stripe_lds_bytes(M, group, gps, 16) > (size_t)stripe_lds_limit() ||
+                           (unsigned long long)gps * (group / 8) * N * 4ull >= 0x7F000000ull))
+            gps = (gps + 1) / 2;
+        S = (G + gps - 1) / gps;
+        if (S > 255 || stripe_lds_bytes(M, group, gps, 16) > (size_t)stripe_lds_limit()) return W4A16_ERR_UNSUPPORTED;
+        // waves: each should own at least four blocks of 16 k; twelve measured best on the large shapes (ten to
+        // sixteen are within 3 % of each other)
+        const long long nblocks = (long long)gps * (group / 16);
+        int waves = (int)(nblocks / 4);
+        waves = waves < 1 ? 1 : (waves > 12 ? 12 : waves);
+        if (const char *e = getenv("W4A16_STRIPE_WAVES")) {  // tuning aid for sweeps, not part of the contract
+            const int w = atoi(e);
+            if (w >= 1 && w <= 16 && stripe_lds_bytes(M, group, gps, w) <= (size_t)stripe_lds_limit()) waves = w;
+        }
+        p->waves_k = waves;
+        p->threads = waves * 64;
+        p->split = S;
+        p->groups_per_split = gps;
+        p->workgroups = (int)(tiles * S);
+        p->workspace_bytes = S > 1 ? (size_t)M * N * sizeof(unsigned long long) : 0;
+        return W4A16_OK;
+    }
     if (kernel == W4A16_KERNEL_WAVE_SPLIT) {
         p->tile_n = (N + 63) / 64 >= cus ? 64 : 32;
         p->tile_m = 4;
@@ -169,6 +205,32 @@ int ensure_workspace(int dev, size_t bytes, void **out)
     return W4A16_OK;
 }
 
+// The STRIPE family's accumulator: grown on demand, cleared once when allocated (on `stream`,
+// ahead of the launch that first uses it); every launch leaves it all zero again.
+int ensure_accumulator(int dev, size_t bytes, hipStream_t stream, void **out)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState &d = g_dev[dev];
+    if (d.acc_bytes < bytes) {
+        if (d.acc) {
+            hipError_t e = hipFree(d.acc);
+            d.acc = nullptr;
+            d.acc_bytes = 0;
+            if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_WORKSPACE; }
+        }
+        size_t want = bytes < (1u << 20) ? (1u << 20) : bytes + bytes / 4;
+        void *ptr = nullptr;
+        hipError_t e = hipMalloc(&ptr, want);
+        if (e != hipSuccess) { note_hip_error(e); (void)hipGetLastError(); return W4A16_ERR_WORKSPACE; }
+        e = launch_stripe_clear(static_cast<unsigned long long *>(ptr), want / 8, stream);
+        if (e != hipSuccess) { note_hip_error(e); (void)hipFree(ptr); return W4A16_ERR_HIP; }
+        d.acc = ptr;
+        d.acc_bytes = want;
+    }
+    *out = d.acc;
+    return W4A16_OK;
+}
+
 int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *zeros, int group, int M, int N, int K,
         void *Y, void *stream, int kernel, int split, void *user_ws, size_t user_ws_bytes, bool user_ws_given)
 {
@@ -186,11 +248,19 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
     rc = make_plan(M, N, K, group, kernel, split, compute_units(dev), &plan);
     if (rc) return rc;
 
+    hipStream_t st = static_cast<hipStream_t>(stream);
     void *ws = nullptr;
     if (plan.workspace_bytes) {
         if (user_ws_given) {
             if (user_ws_bytes < plan.workspace_bytes) return W4A16_ERR_WORKSPACE;
             ws = user_ws;
+            if (plan.kernel == W4A16_KERNEL_STRIPE) {  // a caller's workspace comes uninitialised
+                hipError_t e = launch_stripe_clear(static_cast<unsigned long long *>(ws), (size_t)M * N, st);
+                if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+            }
+        } else if (plan.kernel == W4A16_KERNEL_STRIPE) {
+            rc = ensure_accumulator(dev, plan.workspace_bytes, st, &ws);
+            if (rc) return rc;
         } else {
             rc = ensure_workspace(dev, plan.workspace_bytes, &ws);
             if (rc) return rc;
@@ -208,12 +278,13 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
     a.split = plan.split;
     a.groups_per_split = plan.groups_per_split;
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st)
-                 : plan.kernel == W4A16_KERNEL_MFMA_ROWS ? launch_mfma_rows(a, plan.tile_m, st)
-                                                         : launch_mfma_reg(a, st);
+    hipError_t e = plan.kernel == W4A16_KERNEL_STRIPE
+                       ? launch_stripe(a, static_cast<unsigned long long *>(ws), plan.waves_k, st)
+                   : plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st)
+                   : plan.kernel == W4A16_KERNEL_MFMA_ROWS  ? launch_mfma_rows(a, plan.tile_m, st)
+                                                            : launch_mfma_reg(a, st);
     if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
-    if (plan.split > 1) {
+    if (plan.split > 1 && plan.kernel != W4A16_KERNEL_STRIPE) {
         e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);
         if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
     }
@@ -290,14 +361,17 @@ void w4a16_shutdown(void)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     for (int d = 0; d < kMaxDevices; ++d) {
-        if (!g_dev[d].ws) continue;
+        if (!g_dev[d].ws && !g_dev[d].acc) continue;
         int prev = -1;
         if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(d) == hipSuccess) {
-            (void)hipFree(g_dev[d].ws);
+            if (g_dev[d].ws) (void)hipFree(g_dev[d].ws);
+            if (g_dev[d].acc) (void)hipFree(g_dev[d].acc);
             (void)hipSetDevice(prev);
         }
         g_dev[d].ws = nullptr;
         g_dev[d].ws_bytes = 0;
+        g_dev[d].acc = nullptr;
+        g_dev[d].acc_bytes = 0;
     }
 }
 

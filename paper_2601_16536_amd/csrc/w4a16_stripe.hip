@@ -1,0 +1,330 @@
+// W4A16 multiply for the decode case (M <= 4): one workgroup per (256-column
+// stripe, K slice).  Every wave-wide load reads one whole KiB of one packed row
+// (64 lanes x 4 words); the waves of a workgroup own contiguous runs of the
+// slice's packed rows.
+//
+// This is Algorithm 1's Split-K at two levels.  Inside a workgroup the waves'
+// runs of K are Phase 2's slices (C_i = A * B_i) and their sums meet in LDS.
+// Across workgroups (S > 1) the per-slice sums meet in a 64-bit fixed-point
+// accumulator per output element (Phase 3: C = sum_i C_i, then the cast to
+// FP16): one returning atomic add carries the value and an arrival count, the
+// last arriver casts and stores Y and clears the accumulator.  Integer adds
+// commute, so the result does not depend on the arrival order, and there is no
+// second launch.
+//
+// Why stripes of 256 columns: with one 128-byte-wide column tile per workgroup
+// the 128-byte lines of one class of address bits 7-9 are served ~13 % slower
+// than the others on this GPU and the workgroups that own them set the kernel
+// time.  A 1 KiB-wide stripe holds every class of line in equal parts.  Measured
+// on K = 28672, N = 8192 and kept: contiguous runs of rows per wave (interleaving
+// the waves' rows costs 10 %), two blocks of two rows in flight per wave (both
+// deeper and shallower prefetch are slower), nontemporal weight loads (+5 %).
+//
+// MFMA operand trick for M <= 4: all 64 lanes hold words of the SAME packed row
+// (eight k) but of different columns.  Lane group g (lanes 16g..16g+15) feeds its
+// words as k-group g of the 16x16x32 MFMA's B operand; the A operand holds row r
+// of X in MFMA row 4g+r for k-group g only and zeros elsewhere, so result row
+// 4g+r, column j -- which is exactly what lane (g, j) holds as element r -- is
+// the dot product of X row r with lane (g, j)'s own column.
+//
+// The MFMA sums P = 2^-24 sum_k x_k q_k run over all of a wave's rows of one
+// quantisation group before scale and zero point are applied (Eq. 2, in fp32).
+// X (as A-operand entries) and the sums of x per block are staged in LDS once,
+// behind one barrier.  Scales and zero points travel with the weight blocks
+// (one 8-byte and one 4-byte load per block, mostly cache hits): staging them
+// in LDS ahead of the loop instead was measured 1 us slower, because the waves
+// then sit at the barrier on cold loads with only their first blocks in flight.
+#include "w4a16_device.h"
+#include "w4a16_internal.h"
+
+namespace w4a16 {
+namespace {
+
+constexpr int kStripe = 256;    // columns per workgroup: 64 lanes x 4 words
+constexpr int kBlockRows = 2;   // packed rows per block (16 k)
+constexpr int kRing = 2;        // blocks in flight per wave
+constexpr int kLdsLimit = 144 * 1024;
+
+// LDS map of one workgroup (bytes), for `rows` packed rows.
+struct LdsMap {
+    size_t xs, zero, bs, total;
+};
+__host__ __device__ inline LdsMap lds_map(int mrows, int rows)
+{
+    LdsMap m;
+    m.xs = 0;                                                  // [rows][mrows] A-operand entries of 16 bytes
+    m.zero = (size_t)rows * mrows * 16;                        // one all-zero entry
+    m.bs = m.zero + 16;                                        // [rows / kBlockRows][mrows] fp32 sums of x
+    m.total = m.bs + (size_t)(rows / kBlockRows) * mrows * 4;
+    return m;
+}
+
+// Fixed-point form of a slice sum for the cross-workgroup accumulator: the value
+// in units of 2^-24 (clamped far outside the FP16 range), biased to be positive,
+// in bits 0-55; one arrival in bits 56-63.  Up to 255 slices cannot carry into
+// the count.
+constexpr float kFixScale = 16777216.0f;            // 2^24
+constexpr float kFixClamp = 2097152.0f;             // 2^21
+constexpr unsigned long long kFixBias = 1ull << 46;
+constexpr unsigned long long kFixOne = 1ull << 56;
+
+__device__ __forceinline__ unsigned long long to_fixed(float v)
+{
+    v = fminf(fmaxf(v, -kFixClamp), kFixClamp);
+    const long long fx = (long long)__builtin_rintf(v * kFixScale);  // |v| <= 2^21: the product is exact, |fx| <= 2^45
+    return (unsigned long long)(fx + (long long)kFixBias) + kFixOne;
+}
+
+__device__ __forceinline__ float from_fixed(unsigned long long total)
+{
+    const unsigned long long cnt = total >> 56;
+    const long long fx = (long long)(total & (kFixOne - 1)) - (long long)(cnt * kFixBias);
+    return (float)((double)fx * (1.0 / 16777216.0));
+}
+
+template <int MROWS>
+__global__ __launch_bounds__(1024) void stripe_kernel(const GemmArgs a, unsigned long long *__restrict__ acc)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int waves = blockDim.x >> 6;
+    const int nstripes = (a.N + kStripe - 1) / kStripe;
+    const int stripe = blockIdx.x % nstripes, slice = blockIdx.x / nstripes;
+    const int col0 = stripe * kStripe + 4 * lane;
+    const bool ok = col0 < a.N;
+
+    // the workgroup's K slice: groups, packed rows, blocks; this wave's run of blocks
+    const int gbeg = slice * a.groups_per_split;
+    int gend = gbeg + a.groups_per_split;
+    if (gend > a.K / a.group) gend = a.K / a.group;
+    const int groups = gend - gbeg;
+    const int rows = groups * (a.group / 8);
+    const int row_base = gbeg * (a.group / 8);
+    const uint32_t nblocks = (uint32_t)rows / kBlockRows;
+    const uint32_t bpg = (uint32_t)a.group / (8 * kBlockRows);  // blocks per group
+    const uint32_t wb0 = (uint32_t)((unsigned long long)nblocks * wave / waves);
+    const uint32_t wb1 = (uint32_t)((unsigned long long)nblocks * (wave + 1) / waves);
+
+    const uint32_t row_w = (uint32_t)a.N * 4u, row_s = (uint32_t)a.N * 2u, row_z = (uint32_t)(a.N >> 3) * 4u;
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t *>(a.Wp) + (size_t)row_base * a.N, 0, (uint32_t)rows * row_w, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(a.scales) + (size_t)gbeg * a.N, 0, (uint32_t)groups * row_s, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t *>(a.Zp) + (size_t)gbeg * (a.N >> 3), 0, (uint32_t)groups * row_z, kRawBuffer);
+    const uint32_t vw = ok ? (uint32_t)col0 * 4u : kOutOfRange;
+    const uint32_t vs = ok ? (uint32_t)col0 * 2u : kOutOfRange;
+    const uint32_t vz = ok ? (uint32_t)(col0 >> 3) * 4u : kOutOfRange;
+
+    // Block b of the slice, with the scales and zero points of its group, if b < wb1, else nothing (the
+    // per-lane offset, which the hardware range-checks against the slice size, is pushed out of range:
+    // zeros, no traffic).  Weights are read once: nontemporal.
+    struct Block {
+        uint4_t w[kBlockRows];
+        uint2_t sc;
+        uint32_t zw;
+    };
+    Block buf[kRing];
+    auto load_block = [&](Block &r, uint32_t b, uint32_t g) {
+        const bool valid = b < wb1;
+        const uint32_t base = valid ? b * kBlockRows * row_w : 0u;
+        const uint32_t gu = __builtin_amdgcn_readfirstlane(valid ? g : 0u);  // wave-uniform: keeps the row offsets scalar
+        r.sc = __builtin_amdgcn_raw_buffer_load_b64(rs, valid ? vs : kOutOfRange, gu * row_s, 0);
+        r.zw = __builtin_amdgcn_raw_buffer_load_b32(rz, valid ? vz : kOutOfRange, gu * row_z, 0);
+#pragma unroll
+        for (int t = 0; t < kBlockRows; ++t)
+            r.w[t] = __builtin_amdgcn_raw_buffer_load_b128(rw, valid ? vw : kOutOfRange, base + (uint32_t)t * row_w, 2);
+    };
+    // ---- stage X and its block sums ----
+    const LdsMap lm = lds_map(MROWS, rows);
+    uint4_t *xs = reinterpret_cast<uint4_t *>(smem + lm.xs);
+    float *bs = reinterpret_cast<float *>(smem + lm.bs);
+    // X goes first: loads return in order, and X (mostly cache hits) must not queue behind the first
+    // weight blocks, which come from DRAM.  Two entries per thread are requested ahead of the weights
+    // (all of X for M = 1 and 2 at the tuned shapes); what is left follows behind them.
+    const int nthreads = blockDim.x;
+    const int total = rows * MROWS;  // even: lanes (idx, idx ^ 1) hold one block of one row of X
+    auto x_load = [&](int idx) {
+        const int m = idx / rows, kb = idx - m * rows;
+        uint4_t d = {0u, 0u, 0u, 0u};
+        if (idx < total && m < a.M) d = *reinterpret_cast<const uint4_t *>(a.X + (size_t)m * a.K + (size_t)(row_base + kb) * 8);
+        return d;
+    };
+    auto x_store = [&](int idx, uint4_t d) {
+        const int m = idx / rows, kb = idx - m * rows;
+        float sum = sum8(d);
+        sum += __shfl_xor(sum, 1, 64);
+        if (idx < total) {
+            xs[kb * MROWS + m] = permute_x(d);
+            if ((kb & 1) == 0) bs[(kb >> 1) * MROWS + m] = sum;
+        }
+    };
+    const bool pre0 = wave * 64 < total, pre1 = nthreads + wave * 64 < total;  // wave-uniform
+    uint4_t d0 = {0u, 0u, 0u, 0u}, d1 = {0u, 0u, 0u, 0u};
+    if (pre0) d0 = x_load(tid);
+    if (pre1) d1 = x_load(nthreads + tid);
+
+    // (lg, lnext): group of the next block to load and the first block of the group after it
+    uint32_t lg = wb0 / bpg, lnext = (lg + 1) * bpg;
+#pragma unroll
+    for (int p = 0; p < kRing; ++p) {
+        load_block(buf[p], wb0 + p, lg);
+        if (wb0 + p + 1 == lnext) { ++lg; lnext += bpg; }
+    }
+
+    if (pre0) x_store(tid, d0);
+    if (pre1) x_store(nthreads + tid, d1);
+    for (int base = 2 * nthreads + wave * 64; base < total; base += nthreads) x_store(base + lane, x_load(base + lane));
+    if (tid == 0) *reinterpret_cast<uint4_t *>(smem + lm.zero) = (uint4_t){0u, 0u, 0u, 0u};
+    __syncthreads();
+
+    // this lane's A-operand entry of packed row 0: X row r = j - 4 g when 0 <= r < MROWS, else the zero entry
+    const int g4 = lane >> 4, j = lane & 15;
+    const int r = j - 4 * g4;
+    const bool has_row = r >= 0 && r < MROWS;
+    const uint32_t xa0 = has_row ? (uint32_t)(lm.xs + r * 16) : (uint32_t)lm.zero;
+    const uint32_t xstep = has_row ? (uint32_t)(MROWS * 16) : 0u;  // bytes per packed row
+    const uint32_t zsh = (uint32_t)(col0 & 7) * 4u;                // this lane's four nibbles in its zero-point word
+
+    float tot[4][MROWS];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int i = 0; i < MROWS; ++i) tot[c][i] = 0.f;
+    float4_t part[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) part[c] = (float4_t){0.f, 0.f, 0.f, 0.f};
+    float xsum[MROWS];
+#pragma unroll
+    for (int i = 0; i < MROWS; ++i) xsum[i] = 0.f;
+    const Masks masks = make_masks();
+
+    uint32_t gnext = (wb0 / bpg + 1) * bpg;  // first block of the group after the current one
+
+    for (uint32_t b = wb0; b < wb1; b += kRing) {
+#pragma unroll
+        for (int p = 0; p < kRing; ++p) {
+            const uint32_t cur = b + p;
+            if (cur < wb1) {
+                // Loads return in order and the block's scales and zero points were issued ahead of its
+                // weights.  Naming them here, used or not, tells the compiler that they have landed, so that
+                // reloading their registers below needs no wait on younger loads.
+                asm volatile("" ::"v"(buf[p].sc[0]), "v"(buf[p].sc[1]), "v"(buf[p].zw));
+#pragma unroll
+                for (int t = 0; t < kBlockRows; ++t) {
+                    H8 x;
+                    x.u = *reinterpret_cast<const uint4_t *>(smem + xa0 + (cur * kBlockRows + t) * xstep);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        part[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, unpack8(buf[p].w[t][c], masks), part[c], 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < MROWS; ++i) xsum[i] += bs[cur * MROWS + i];
+                if (cur + 1 == gnext || cur + 1 == wb1) {
+                    // the wave's rows of this group are done: scale and zero point (Eq. 2)
+                    H2 s01, s23;
+                    s01.u = buf[p].sc[0];
+                    s23.u = buf[p].sc[1];
+                    const float s[4] = {(float)s01.h[0], (float)s01.h[1], (float)s23.h[0], (float)s23.h[1]};
+                    const uint32_t zw = buf[p].zw >> zsh;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float z = (float)((zw >> (4 * c)) & 15u);
+#pragma unroll
+                        for (int i = 0; i < MROWS; ++i) tot[c][i] = apply_scale_zero(tot[c][i], s[c], z, part[c][i], xsum[i]);
+                        part[c] = (float4_t){0.f, 0.f, 0.f, 0.f};
+                    }
+#pragma unroll
+                    for (int i = 0; i < MROWS; ++i) xsum[i] = 0.f;
+                    gnext += bpg;
+                }
+            }
+            load_block(buf[p], cur + kRing, lg);
+            if (cur + kRing + 1 == lnext) { ++lg; lnext += bpg; }
+        }
+    }
+
+    // Sum over the waves in wave order: red[wave][m][column of the stripe].
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(smem);
+#pragma unroll
+    for (int i = 0; i < MROWS; ++i)
+        *reinterpret_cast<float4_t *>(red + ((size_t)(wave * MROWS + i) * kStripe + 4 * lane)) =
+            (float4_t){tot[0][i], tot[1][i], tot[2][i], tot[3][i]};
+    __syncthreads();
+    for (int o = tid; o < MROWS * kStripe; o += blockDim.x) {
+        const int m = o / kStripe, c = o - m * kStripe;
+        const int col = stripe * kStripe + c;
+        if (m >= a.M || col >= a.N) continue;
+        float v = red[m * kStripe + c];
+        for (int w = 1; w < waves; ++w) v += red[(size_t)(w * MROWS + m) * kStripe + c];
+        const size_t out = (size_t)m * a.N + col;
+        if (a.split == 1) {
+            a.Y[out] = (uint16_t)(pack_half2(v, 0.f) & 0xFFFFu);
+        } else {
+            const unsigned long long add = to_fixed(v);
+            const unsigned long long total = __hip_atomic_fetch_add(acc + out, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+            if ((total >> 56) == (unsigned long long)a.split) {
+                a.Y[out] = (uint16_t)(pack_half2(from_fixed(total), 0.f) & 0xFFFFu);
+                __hip_atomic_store(acc + out, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void clear_kernel(unsigned long long *p, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
+}
+
+int mrows_of(int M) { return M == 1 ? 1 : (M == 2 ? 2 : 4); }
+
+template <int MROWS>
+hipError_t launch_m(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream)
+{
+    const size_t lds = stripe_lds_bytes(a.M, a.group, a.groups_per_split, waves);
+    if (lds > (size_t)stripe_lds_limit()) return hipErrorInvalidValue;
+    const unsigned long long rows = (unsigned long long)a.groups_per_split * (a.group / 8);
+    if (rows * a.N * 4ull >= 0x7F000000ull) return hipErrorInvalidValue;  // slice-relative 32-bit buffer offsets
+    const int nstripes = (a.N + kStripe - 1) / kStripe;
+    if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<MROWS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, stripe_lds_limit());
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((stripe_kernel<MROWS>), dim3(nstripes * a.split), dim3(waves * 64), lds, stream, a, acc);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int stripe_lds_limit() { return kLdsLimit; }
+
+size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves)
+{
+    const int mrows = mrows_of(M);
+    const size_t stage = lds_map(mrows, groups_per_split * (group / 8)).total;
+    const size_t red = (size_t)waves * mrows * kStripe * 4;
+    return stage > red ? stage : red;
+}
+
+hipError_t launch_stripe_clear(unsigned long long *acc, size_t n, hipStream_t stream)
+{
+    hipLaunchKernelGGL(clear_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, acc, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_stripe(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream)
+{
+    if (a.M > 4 || waves < 1 || waves > 16 || a.group % (8 * kBlockRows) != 0) return hipErrorInvalidValue;
+    if (a.split > 1 && (!acc || a.split > 255)) return hipErrorInvalidValue;
+    if (a.M == 1) return launch_m<1>(a, acc, waves, stream);
+    if (a.M == 2) return launch_m<2>(a, acc, waves, stream);
+    return launch_m<4>(a, acc, waves, stream);
+}
+
+}  // namespace w4a16

@@ -77,7 +77,8 @@ def test_small_shapes_every_split(gpu, M, K, N, group):
     X, Wp, s, Zp = wl.make(M, K, N, index=1000 + M + K + N, group=group)
     ref = orc.gemm(X, Wp, s, Zp, group)
     G = K // group
-    kernels = [binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS] + ([binding.KERNEL_WAVE_SPLIT] if M <= 4 else [])
+    kernels = [binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS] + (
+        [binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE] if M <= 4 else [])
     for kernel in kernels:
         for split in sorted({0, 1, 2, 3, G}):
             if split > G:
@@ -102,8 +103,9 @@ def test_integer_case_bit_exact(gpu):
     say("integer exact")
     Y = run_gpu(gpu, X, Wp, s, Zp, group)
     assert np.array_equal(Y.astype(np.float64), ref)
-    Y = run_gpu(gpu, X[:3], Wp, s, Zp, group, kernel=0)
-    assert np.array_equal(Y.astype(np.float64), ref[:3])
+    for kernel in (0, 3):
+        Y = run_gpu(gpu, X[:3], Wp, s, Zp, group, kernel=kernel)
+        assert np.array_equal(Y.astype(np.float64), ref[:3])
 
 
 def test_integer_case_bit_exact_with_zero_points_and_splits(gpu):
@@ -122,7 +124,7 @@ def test_integer_case_bit_exact_with_zero_points_and_splits(gpu):
     Wp, Zp = wl.pack_along_k(q), wl.pack_along_n(z)
     ref = orc.gemm(X, Wp, s, Zp, group)
     assert np.abs(ref).max() < 2048 and np.array_equal(ref, np.round(ref))
-    for kernel in (0, 1):
+    for kernel in (0, 1, 3):
         for split in (1, 2, 4):
             say("integer exact zp", kernel, split)
             Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=kernel, split=split)
@@ -142,9 +144,10 @@ def test_one_hot_rows_return_weight_rows(gpu):
     want = w[ks].astype(np.float16)  # exact fp32 weight, one rounding to fp16
     Y = run_gpu(gpu, X, Wp, s, Zp, group)
     assert np.array_equal(Y, want)
-    for i in range(0, len(ks), 4):  # the M <= 4 kernel, four rows at a time
-        Y = run_gpu(gpu, X[i:i + 4], Wp, s, Zp, group, kernel=0)
-        assert np.array_equal(Y, want[i:i + 4])
+    for i in range(0, len(ks), 4):  # the M <= 4 kernels, four rows at a time
+        for kernel, split in ((0, 0), (3, 1), (3, 2)):
+            Y = run_gpu(gpu, X[i:i + 4], Wp, s, Zp, group, kernel=kernel, split=split)
+            assert np.array_equal(Y, want[i:i + 4])
 
 
 def test_closed_forms_on_gpu(gpu):
@@ -184,7 +187,8 @@ def test_symmetric_int4_as_zero_point_eight(gpu):
 
 def binding_kernels(gpu):
     _, binding = gpu
-    return (binding.KERNEL_AUTO, binding.KERNEL_WAVE_SPLIT, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS)
+    return (binding.KERNEL_AUTO, binding.KERNEL_WAVE_SPLIT, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS,
+            binding.KERNEL_STRIPE)
 
 
 def test_deterministic_and_split_invariant(gpu):
@@ -229,6 +233,39 @@ def test_non_default_stream_and_caller_workspace(gpu):
     with pytest.raises(binding.W4A16Error) as e:
         binding.gemm_ws(dX, dW, dS, dZ, group, ws[:1024], split=8)
     assert e.value.status == binding.ERR_WORKSPACE
+
+
+def test_stripe_accumulator_is_left_clean(gpu):
+    """The STRIPE family adds the K slices of different workgroups into a 64-bit fixed-point accumulator
+    (one atomic add each) that the last arriver clears: calls of different shapes and splits in a row, on the
+    library's own accumulator and on a caller's (poisoned) one, must each be right."""
+    torch, binding = gpu
+    cases = [(1, 4096, 1024, 8), (4, 2048, 520, 3), (2, 4096, 264, 32), (1, 4096, 1024, 5), (3, 1024, 4104, 2)]
+    data = {}
+    for M, K, N, S in cases:
+        if (M, K, N) not in data:
+            X, Wp, s, Zp = wl.make(M, K, N, index=500 + M + K + N)
+            data[(M, K, N)] = (binding.to_device(X, Wp, s, Zp), orc.gemm(X, Wp, s, Zp, wl.GROUP))
+    for rep in range(3):
+        for M, K, N, S in cases:
+            (dX, dW, dS, dZ), ref = data[(M, K, N)]
+            say("stripe clean", rep, M, K, N, S)
+            Y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+            binding.gemm_ex(dX, dW, dS, dZ, wl.GROUP, kernel=binding.KERNEL_STRIPE, split=S, out=Y)
+            torch.cuda.synchronize()
+            assert err_ratio(Y.cpu().numpy(), ref) <= 1.0
+    M, K, N, S = cases[0]
+    (dX, dW, dS, dZ), ref = data[(M, K, N)]
+    plan = binding.query_plan(M, N, K, wl.GROUP, binding.KERNEL_STRIPE, S)
+    assert plan["workspace_bytes"] == M * N * 8
+    ws = torch.full((plan["workspace_bytes"] + 256,), 0xFF, dtype=torch.uint8, device="cuda")
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + plan["workspace_bytes"]]
+    for rep in range(2):
+        Y = binding.gemm_ws(dX, dW, dS, dZ, wl.GROUP, ws, kernel=binding.KERNEL_STRIPE, split=S)
+        torch.cuda.synchronize()
+        assert err_ratio(Y.cpu().numpy(), ref) <= 1.0
+        assert int(ws.view(torch.int64).abs().max().item()) == 0  # cleared by the last arrivers
 
 
 def test_error_codes_leave_output_untouched(gpu):

@@ -62,7 +62,7 @@ def test_argument_checks_need_no_gpu(binding):
     with pytest.raises(binding.W4A16Error):
         binding.query_plan(1, 64, 256, 128, split=3)  # only two groups
     with pytest.raises(binding.W4A16Error):
-        binding.query_plan(1, 64, 256, 128, kernel=3)
+        binding.query_plan(1, 64, 256, 128, kernel=4)
 
 
 SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336), (16, 4096, 14336), (1, 8192, 28672),
@@ -73,7 +73,8 @@ SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336),
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_plans_are_well_formed(binding, M, N, K):
     G = K // 128
-    for kernel in (binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS) + ((binding.KERNEL_WAVE_SPLIT,) if M <= 4 else ()):
+    for kernel in (binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS) + (
+            (binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE) if M <= 4 else ()):
         for split in sorted({0, 1, 2, 7, G}):
             if split > G:
                 continue
@@ -83,19 +84,25 @@ def test_plans_are_well_formed(binding, M, N, K):
             assert S * gps >= G and (S - 1) * gps < G  # slices cover K, none empty
             if split:
                 assert S <= split
-            assert p["workspace_bytes"] == (S * M * N * 4 if S > 1 else 0)
-            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (0 if M <= 4 else (1 if M <= 16 else 2)))
+            stripe = p["kernel"] == binding.KERNEL_STRIPE
+            assert p["workspace_bytes"] == ((M * N * 8 if stripe else S * M * N * 4) if S > 1 else 0)
+            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (3 if M <= 4 else (1 if M <= 16 else 2)))
             tiles_n = -(-N // p["tile_n"])
-            tiles_m = -(-M // p["tile_m"]) if p["kernel"] != binding.KERNEL_WAVE_SPLIT else 1
+            tiles_m = -(-M // p["tile_m"]) if p["kernel"] not in (binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE) else 1
             assert p["workgroups"] == tiles_n * tiles_m * S
-            assert p["threads"] in (256, 1024) and p["waves_k"] in (1, 16)
+            if stripe:
+                assert S <= 255 and 1 <= p["waves_k"] <= 16 and p["threads"] == 64 * p["waves_k"] and p["tile_n"] == 256
+            else:
+                assert p["threads"] in (256, 1024) and p["waves_k"] in (1, 16)
     assert binding.workspace_bytes(M, N, K, 128) >= binding.query_plan(M, N, K, 128)["workspace_bytes"]
 
 
 def test_headline_plan_is_one_launch(binding):
+    """M = 1, K = 28672, N = 8192: 32 stripes x 8 K slices = one workgroup per compute unit, the slices meet in
+    the fixed-point accumulator (8 bytes per output), no second pass."""
     p = binding.query_plan(1, 8192, 28672, 128)
-    assert p["kernel"] == binding.KERNEL_WAVE_SPLIT and p["split"] == 1 and p["workspace_bytes"] == 0
-    assert p["workgroups"] == 256 and p["waves_k"] == 16
+    assert p["kernel"] == binding.KERNEL_STRIPE and p["split"] == 8 and p["workspace_bytes"] == 8192 * 8
+    assert p["workgroups"] == 256 and p["groups_per_split"] == 28
 
 
 def test_product_does_not_touch_the_oracle():
