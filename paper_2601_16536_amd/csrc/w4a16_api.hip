@@ -91,49 +91,62 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // M > 16 (MFMA_ROWS): the same tiles with 32 or 64 rows of X per workgroup, so
 //   that each unpacked weight word feeds 2 or 4 MFMAs and W is read once per 32
 //   or 64 rows.
+// How the K slices of different workgroups of a STRIPE plan meet: in the 64-bit fixed-point accumulator (one
+// returning atomic add per output and slice; the GPU retires ~150 of them per ns-thousand, measured) while
+// that is cheaper than a second launch, else in the FP32 workspace and the second pass.
+bool stripe_meets_in_accumulator(int M, int N, int S)
+{
+    return S <= 255 && (long long)S * M * N <= 320 * 1024;
+}
+
 int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4a16_plan *p)
 {
     const int G = K / group;
     if (kernel == W4A16_KERNEL_AUTO)
-        kernel = M <= 4 ? W4A16_KERNEL_STRIPE : (M <= 16 ? W4A16_KERNEL_MFMA_REG : W4A16_KERNEL_MFMA_ROWS);
+        kernel = M <= 16 ? W4A16_KERNEL_STRIPE : W4A16_KERNEL_MFMA_ROWS;
     if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG && kernel != W4A16_KERNEL_MFMA_ROWS &&
         kernel != W4A16_KERNEL_STRIPE)
         return W4A16_ERR_UNSUPPORTED;
-    if ((kernel == W4A16_KERNEL_WAVE_SPLIT || kernel == W4A16_KERNEL_STRIPE) && M > 4) return W4A16_ERR_UNSUPPORTED;
+    if (kernel == W4A16_KERNEL_WAVE_SPLIT && M > 4) return W4A16_ERR_UNSUPPORTED;
+    if (kernel == W4A16_KERNEL_STRIPE && M > 16) return W4A16_ERR_UNSUPPORTED;
     if (split < 0 || split > G) return W4A16_ERR_UNSUPPORTED;
     p->kernel = kernel;
     long long tiles;
     int S = split;
     if (kernel == W4A16_KERNEL_STRIPE) {
         p->tile_n = 256;
-        p->tile_m = 4;
+        p->tile_m = M <= 4 ? 4 : 16;
         tiles = (N + 255) / 256;
+        const int wmin = stripe_min_waves(M), wmax = stripe_max_waves(M);
         if (S == 0) S = (int)((cus + tiles / 2) / tiles);  // one workgroup per compute unit
-        if (S > 255) S = 255;                               // arrival count of the accumulator
         if (S < 1) S = 1;
         if (S > G) S = G;
         int gps = (G + S - 1) / S;
         // the slice's X rows must fit the workgroup's LDS and its weights a 31-bit buffer: shorten the slice if not
-        while (gps > 1 && (stripe_lds_bytes(M, group, gps, 16) > (size_t)stripe_lds_limit() ||
+        while (gps > 1 && (stripe_lds_bytes(M, group, gps, wmin) > (size_t)stripe_lds_limit() ||
                            (unsigned long long)gps * (group / 8) * N * 4ull >= 0x7F000000ull))
             gps = (gps + 1) / 2;
         S = (G + gps - 1) / gps;
-        if (S > 255 || stripe_lds_bytes(M, group, gps, 16) > (size_t)stripe_lds_limit()) return W4A16_ERR_UNSUPPORTED;
-        // waves: each should own at least four blocks of 16 k; twelve measured best on the large shapes (ten to
-        // sixteen are within 3 % of each other)
+        if (stripe_lds_bytes(M, group, gps, wmin) > (size_t)stripe_lds_limit()) return W4A16_ERR_UNSUPPORTED;
+        // waves: each should own at least four blocks of 16 k; twelve measured best on the large shapes for
+        // M <= 4 (ten to sixteen are within 3 % of each other); the many-row form holds eight at most
         const long long nblocks = (long long)gps * (group / 16);
         int waves = (int)(nblocks / 4);
-        waves = waves < 1 ? 1 : (waves > 12 ? 12 : waves);
+        const int wbest = wmax > 12 ? 12 : wmax;
+        waves = waves < wmin ? wmin : (waves > wbest ? wbest : waves);
         if (const char *e = getenv("W4A16_STRIPE_WAVES")) {  // tuning aid for sweeps, not part of the contract
             const int w = atoi(e);
-            if (w >= 1 && w <= 16 && stripe_lds_bytes(M, group, gps, w) <= (size_t)stripe_lds_limit()) waves = w;
+            if (w >= wmin && w <= wmax) waves = w;
         }
+        while (waves > wmin && stripe_lds_bytes(M, group, gps, waves) > (size_t)stripe_lds_limit()) --waves;
         p->waves_k = waves;
         p->threads = waves * 64;
         p->split = S;
         p->groups_per_split = gps;
         p->workgroups = (int)(tiles * S);
-        p->workspace_bytes = S > 1 ? (size_t)M * N * sizeof(unsigned long long) : 0;
+        p->workspace_bytes = S == 1 ? 0
+                             : stripe_meets_in_accumulator(M, N, S) ? (size_t)M * N * sizeof(unsigned long long)
+                                                                    : (size_t)S * M * N * sizeof(float);
         return W4A16_OK;
     }
     if (kernel == W4A16_KERNEL_WAVE_SPLIT) {
@@ -250,15 +263,16 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     void *ws = nullptr;
+    const bool in_acc = plan.kernel == W4A16_KERNEL_STRIPE && plan.split > 1 && stripe_meets_in_accumulator(M, N, plan.split);
     if (plan.workspace_bytes) {
         if (user_ws_given) {
             if (user_ws_bytes < plan.workspace_bytes) return W4A16_ERR_WORKSPACE;
             ws = user_ws;
-            if (plan.kernel == W4A16_KERNEL_STRIPE) {  // a caller's workspace comes uninitialised
+            if (in_acc) {  // a caller's workspace comes uninitialised
                 hipError_t e = launch_stripe_clear(static_cast<unsigned long long *>(ws), (size_t)M * N, st);
                 if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
             }
-        } else if (plan.kernel == W4A16_KERNEL_STRIPE) {
+        } else if (in_acc) {
             rc = ensure_accumulator(dev, plan.workspace_bytes, st, &ws);
             if (rc) return rc;
         } else {
@@ -279,12 +293,12 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
     a.groups_per_split = plan.groups_per_split;
 
     hipError_t e = plan.kernel == W4A16_KERNEL_STRIPE
-                       ? launch_stripe(a, static_cast<unsigned long long *>(ws), plan.waves_k, st)
+                       ? launch_stripe(a, in_acc ? static_cast<unsigned long long *>(ws) : nullptr, plan.waves_k, st)
                    : plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st)
                    : plan.kernel == W4A16_KERNEL_MFMA_ROWS  ? launch_mfma_rows(a, plan.tile_m, st)
                                                             : launch_mfma_reg(a, st);
     if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
-    if (plan.split > 1 && plan.kernel != W4A16_KERNEL_STRIPE) {
+    if (plan.split > 1 && !in_acc) {
         e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);
         if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
     }

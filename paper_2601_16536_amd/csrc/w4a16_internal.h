@@ -29,13 +29,16 @@ constexpr int kLdsBudget = 32768;   // bytes of LDS one workgroup stages X into
 hipError_t launch_mfma_reg(const GemmArgs &a, hipStream_t stream);
 hipError_t launch_wave_split(const GemmArgs &a, int tile_n, hipStream_t stream);
 hipError_t launch_mfma_rows(const GemmArgs &a, int tile_m, hipStream_t stream);
-// STRIPE family (M <= 4): `acc` is the fixed-point accumulator [M,N] of 64-bit words that the
-// K slices of different workgroups meet in (all zero before and after every launch; unused when
-// split == 1); `waves` the waves per workgroup (1..16).
+// STRIPE family (M <= 16): `waves` waves per workgroup (stripe_min_waves .. stripe_max_waves).  With
+// split > 1 the K slices of different workgroups meet either in `acc`, the fixed-point accumulator [M,N]
+// of 64-bit words (all zero before and after every launch; split <= 255), or, when acc is null, in
+// a.partials (FP32 [S,M,N]) for the second pass.
 hipError_t launch_stripe(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream);
 hipError_t launch_stripe_clear(unsigned long long *acc, size_t n, hipStream_t stream);
 size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves);  // LDS one workgroup needs
 int stripe_lds_limit();                                                       // most it may use
+int stripe_min_waves(int M);
+int stripe_max_waves(int M);
 // Second pass (Algorithm 1, Phase 3).
 hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream);
 

@@ -1,4 +1,4 @@
-// W4A16 multiply for the decode case (M <= 4): one workgroup per (256-column
+// W4A16 multiply for the decode case (M <= 16): one workgroup per (256-column
 // stripe, K slice).  Every wave-wide load reads one whole KiB of one packed row
 // (64 lanes x 4 words); the waves of a workgroup own contiguous runs of the
 // slice's packed rows.
@@ -27,6 +27,15 @@
 // 4g+r, column j -- which is exactly what lane (g, j) holds as element r -- is
 // the dot product of X row r with lane (g, j)'s own column.
 //
+// For 5 <= M <= 16 the same idea uses the 32x32x16 MFMA: lanes 0-31 feed k-group
+// 0, lanes 32-63 k-group 1; a lane of group g owns result rows 8i + 4g + j
+// (i, j < 4), so the A operand holds row m = 4i + j of X in MFMA row 8i + 4g + j
+// for k-group g only, and the lane's sixteen result elements are the sixteen rows
+// of X against its own column.  With many rows the sums of a slice are large next
+// to the weights it read, so there the slices go to the FP32 workspace [S, M, N]
+// and the second pass (Algorithm 1, Phase 3 as a launch of its own) instead of
+// one atomic add per output and slice.
+//
 // The MFMA sums P = 2^-24 sum_k x_k q_k run over all of a wave's rows of one
 // quantisation group before scale and zero point are applied (Eq. 2, in fp32).
 // X (as A-operand entries) and the sums of x per block are staged in LDS once,
@@ -36,6 +45,7 @@
 // then sit at the barrier on cold loads with only their first blocks in flight.
 #include "w4a16_device.h"
 #include "w4a16_internal.h"
+#include <type_traits>
 
 namespace w4a16 {
 namespace {
@@ -43,6 +53,7 @@ namespace {
 constexpr int kStripe = 256;    // columns per workgroup: 64 lanes x 4 words
 constexpr int kBlockRows = 2;   // packed rows per block (16 k)
 constexpr int kRing = 2;        // blocks in flight per wave
+constexpr int kStageBatch = 4;  // 16-byte entries of X a thread requests at a time beyond the first ones
 constexpr int kLdsLimit = 144 * 1024;
 
 // LDS map of one workgroup (bytes), for `rows` packed rows.
@@ -82,8 +93,90 @@ __device__ __forceinline__ float from_fixed(unsigned long long total)
     return (float)((double)fx * (1.0 / 16777216.0));
 }
 
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
 template <int MROWS>
-__global__ __launch_bounds__(1024) void stripe_kernel(const GemmArgs a, unsigned long long *__restrict__ acc)
+struct Mma {
+    static constexpr bool wide = MROWS > 4;  // 32x32x16 (sixteen result rows per lane) instead of 16x16x32 (four)
+    typedef typename std::conditional<wide, float16_t, float4_t>::type Acc;
+    static constexpr int kMaxThreads = wide ? 512 : 1024;  // the wide form needs up to 256 registers per lane
+    static constexpr int kMinWaves = wide ? 4 : 1;
+    static constexpr int kRedWaves = wide ? 64 / MROWS : 16;         // waves per round of the final sum, at most
+    static constexpr int kPre = wide ? MROWS : 2;                    // entries of X a thread requests ahead of the weights
+};
+
+// Sum of the waves' results in wave order, `red_waves` waves per round through LDS
+// (red[wave in round][m][column of the stripe]), then the workgroup's finish: Y itself (S = 1), the
+// FP32 partials of the slice, or the fixed-point accumulator.  A thread owns groups of VW neighbouring
+// columns of one row (group o = (row * 256 + column) / VW).
+template <int MROWS>
+struct RowSums {
+    float4_t r[MROWS];  // a lane's four columns, per row of X
+};
+
+template <int MROWS, int VW>
+__device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, unsigned long long *__restrict__ acc, unsigned char *smem,
+                                                  const RowSums<MROWS> tot, int red_waves, int stripe, int slice)
+{
+    typedef float vec_t __attribute__((ext_vector_type(VW)));
+    constexpr int kGroups = MROWS * kStripe / VW;
+    constexpr int kOwn = kGroups / (64 * Mma<MROWS>::kMinWaves);  // groups per thread, at most
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, waves = blockDim.x >> 6;
+    vec_t v[kOwn];
+#pragma unroll
+    for (int k = 0; k < kOwn; ++k) v[k] = vec_t(0.f);
+    const vec_t *red = reinterpret_cast<const vec_t *>(smem);
+    for (int w0 = 0; w0 < waves; w0 += red_waves) {
+        __syncthreads();  // the staged X (first round) or the previous round's sums are no longer needed
+        if (wave >= w0 && wave < w0 + red_waves) {
+            float4_t *mine = reinterpret_cast<float4_t *>(smem) + (size_t)(wave - w0) * MROWS * 64 + lane;
+#pragma unroll
+            for (int i = 0; i < MROWS; ++i) mine[i * 64] = tot.r[i];
+        }
+        __syncthreads();
+        const int nw = waves - w0 < red_waves ? waves - w0 : red_waves;
+#pragma unroll
+        for (int k = 0; k < kOwn; ++k) {
+            if (k * (int)blockDim.x >= kGroups) continue;  // uniform: no thread owns a k-th group
+            const int o = tid + k * (int)blockDim.x;
+            const int oc = o < kGroups ? o : 0;  // threads past the last group read group 0 and store nothing
+            // four reads in flight at a time (past the last wave the last one is read again and not added)
+            for (int w = 0; w < nw; w += 4) {
+                vec_t t0 = red[(size_t)w * kGroups + oc];
+                vec_t t1 = red[(size_t)(w + 1 < nw ? w + 1 : nw - 1) * kGroups + oc];
+                vec_t t2 = red[(size_t)(w + 2 < nw ? w + 2 : nw - 1) * kGroups + oc];
+                vec_t t3 = red[(size_t)(w + 3 < nw ? w + 3 : nw - 1) * kGroups + oc];
+                v[k] += t0;
+                if (w + 1 < nw) v[k] += t1;
+                if (w + 2 < nw) v[k] += t2;
+                if (w + 3 < nw) v[k] += t3;
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kOwn; ++k) {
+        const int o = tid + k * (int)blockDim.x;
+        const int m = o / (kStripe / VW), col = stripe * kStripe + VW * (o % (kStripe / VW));
+        if (o >= kGroups || m >= a.M || col >= a.N) continue;
+        const size_t out = (size_t)m * a.N + col;
+        if constexpr (VW == 4) {
+            if (a.split == 1)
+                *reinterpret_cast<uint2_t *>(a.Y + out) = (uint2_t){pack_half2(v[k][0], v[k][1]), pack_half2(v[k][2], v[k][3])};
+            else
+                *reinterpret_cast<float4_t *>(a.partials + (size_t)slice * a.M * a.N + out) = v[k];
+        } else {
+            const unsigned long long add = to_fixed(v[k][0]);
+            const unsigned long long total = __hip_atomic_fetch_add(acc + out, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+            if ((total >> 56) == (unsigned long long)a.split) {
+                a.Y[out] = (uint16_t)(pack_half2(from_fixed(total), 0.f) & 0xFFFFu);
+                __hip_atomic_store(acc + out, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+template <int MROWS>
+__global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const GemmArgs a, unsigned long long *__restrict__ acc, const int red_waves)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -143,29 +236,34 @@ __global__ __launch_bounds__(1024) void stripe_kernel(const GemmArgs a, unsigned
     uint4_t *xs = reinterpret_cast<uint4_t *>(smem + lm.xs);
     float *bs = reinterpret_cast<float *>(smem + lm.bs);
     // X goes first: loads return in order, and X (mostly cache hits) must not queue behind the first
-    // weight blocks, which come from DRAM.  Two entries per thread are requested ahead of the weights
-    // (all of X for M = 1 and 2 at the tuned shapes); what is left follows behind them.
+    // weight blocks, which come from DRAM.  kPre entries per thread are requested ahead of the weights
+    // (all of the slice's X at the tuned shapes); what is left follows behind them.
     const int nthreads = blockDim.x;
-    const int total = rows * MROWS;  // even: lanes (idx, idx ^ 1) hold one block of one row of X
+    const int total = rows * MROWS;  // a multiple of 2 MROWS: lanes (idx, idx ^ MROWS) hold one block of one row of X
+    // Entry idx = packed row idx / MROWS of X row idx % MROWS: consecutive lanes write consecutive LDS
+    // entries (no bank conflicts) and still read whole cache lines of X (64 / MROWS neighbouring rows' worth).
     auto x_load = [&](int idx) {
-        const int m = idx / rows, kb = idx - m * rows;
+        const int m = idx & (MROWS - 1), kb = idx / MROWS;
         uint4_t d = {0u, 0u, 0u, 0u};
         if (idx < total && m < a.M) d = *reinterpret_cast<const uint4_t *>(a.X + (size_t)m * a.K + (size_t)(row_base + kb) * 8);
         return d;
     };
     auto x_store = [&](int idx, uint4_t d) {
-        const int m = idx / rows, kb = idx - m * rows;
+        const int m = idx & (MROWS - 1), kb = idx / MROWS;
         float sum = sum8(d);
-        sum += __shfl_xor(sum, 1, 64);
+        sum += __shfl_xor(sum, MROWS, 64);  // the other packed row of the block, same row of X
         if (idx < total) {
-            xs[kb * MROWS + m] = permute_x(d);
+            xs[idx] = permute_x(d);
             if ((kb & 1) == 0) bs[(kb >> 1) * MROWS + m] = sum;
         }
     };
-    const bool pre0 = wave * 64 < total, pre1 = nthreads + wave * 64 < total;  // wave-uniform
-    uint4_t d0 = {0u, 0u, 0u, 0u}, d1 = {0u, 0u, 0u, 0u};
-    if (pre0) d0 = x_load(tid);
-    if (pre1) d1 = x_load(nthreads + tid);
+    constexpr int kPre = Mma<MROWS>::kPre;
+    uint4_t pre[kPre];
+#pragma unroll
+    for (int it = 0; it < kPre; ++it) {
+        pre[it] = (uint4_t){0u, 0u, 0u, 0u};
+        if (it * nthreads + wave * 64 < total) pre[it] = x_load(it * nthreads + tid);  // wave-uniform condition
+    }
 
     // (lg, lnext): group of the next block to load and the first block of the group after it
     uint32_t lg = wb0 / bpg, lnext = (lg + 1) * bpg;
@@ -175,16 +273,31 @@ __global__ __launch_bounds__(1024) void stripe_kernel(const GemmArgs a, unsigned
         if (wb0 + p + 1 == lnext) { ++lg; lnext += bpg; }
     }
 
-    if (pre0) x_store(tid, d0);
-    if (pre1) x_store(nthreads + tid, d1);
-    for (int base = 2 * nthreads + wave * 64; base < total; base += nthreads) x_store(base + lane, x_load(base + lane));
+#pragma unroll
+    for (int it = 0; it < kPre; ++it)
+        if (it * nthreads + wave * 64 < total) x_store(it * nthreads + tid, pre[it]);
+    for (int base = kPre * nthreads; base < total; base += kStageBatch * nthreads) {  // long slices only
+        uint4_t d[kStageBatch];
+#pragma unroll
+        for (int it = 0; it < kStageBatch; ++it) d[it] = x_load(base + it * nthreads + tid);
+#pragma unroll
+        for (int it = 0; it < kStageBatch; ++it) x_store(base + it * nthreads + tid, d[it]);
+    }
     if (tid == 0) *reinterpret_cast<uint4_t *>(smem + lm.zero) = (uint4_t){0u, 0u, 0u, 0u};
     __syncthreads();
 
-    // this lane's A-operand entry of packed row 0: X row r = j - 4 g when 0 <= r < MROWS, else the zero entry
-    const int g4 = lane >> 4, j = lane & 15;
-    const int r = j - 4 * g4;
-    const bool has_row = r >= 0 && r < MROWS;
+    // this lane's A-operand entry of packed row 0: a row of X, or the zero entry
+    int r;
+    bool has_row;
+    if constexpr (Mma<MROWS>::wide) {
+        const int g2 = lane >> 5, q = lane & 31;            // MFMA row q, k-group g2
+        r = 4 * (q >> 3) + (q & 3);                         // row 8i + 4g + j holds X row 4i + j ...
+        has_row = ((q >> 2) & 1) == g2 && r < MROWS;        // ... for k-group g only
+    } else {
+        const int g4 = lane >> 4, j = lane & 15;            // MFMA row j, k-group g4
+        r = j - 4 * g4;                                     // row 4g + r holds X row r for k-group g only
+        has_row = r >= 0 && r < MROWS;
+    }
     const uint32_t xa0 = has_row ? (uint32_t)(lm.xs + r * 16) : (uint32_t)lm.zero;
     const uint32_t xstep = has_row ? (uint32_t)(MROWS * 16) : 0u;  // bytes per packed row
     const uint32_t zsh = (uint32_t)(col0 & 7) * 4u;                // this lane's four nibbles in its zero-point word
@@ -194,9 +307,10 @@ __global__ __launch_bounds__(1024) void stripe_kernel(const GemmArgs a, unsigned
     for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int i = 0; i < MROWS; ++i) tot[c][i] = 0.f;
-    float4_t part[4];
+    typedef typename Mma<MROWS>::Acc Acc;
+    Acc part[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) part[c] = (float4_t){0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < 4; ++c) part[c] = Acc(0.f);
     float xsum[MROWS];
 #pragma unroll
     for (int i = 0; i < MROWS; ++i) xsum[i] = 0.f;
@@ -218,8 +332,12 @@ __global__ __launch_bounds__(1024) void stripe_kernel(const GemmArgs a, unsigned
                     H8 x;
                     x.u = *reinterpret_cast<const uint4_t *>(smem + xa0 + (cur * kBlockRows + t) * xstep);
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        part[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, unpack8(buf[p].w[t][c], masks), part[c], 0, 0, 0);
+                    for (int c = 0; c < 4; ++c) {
+                        if constexpr (Mma<MROWS>::wide)
+                            part[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x.h, unpack8(buf[p].w[t][c], masks), part[c], 0, 0, 0);
+                        else
+                            part[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, unpack8(buf[p].w[t][c], masks), part[c], 0, 0, 0);
+                    }
                 }
 #pragma unroll
                 for (int i = 0; i < MROWS; ++i) xsum[i] += bs[cur * MROWS + i];
@@ -235,7 +353,7 @@ __global__ __launch_bounds__(1024) void stripe_kernel(const GemmArgs a, unsigned
                         const float z = (float)((zw >> (4 * c)) & 15u);
 #pragma unroll
                         for (int i = 0; i < MROWS; ++i) tot[c][i] = apply_scale_zero(tot[c][i], s[c], z, part[c][i], xsum[i]);
-                        part[c] = (float4_t){0.f, 0.f, 0.f, 0.f};
+                        part[c] = Acc(0.f);
                     }
 #pragma unroll
                     for (int i = 0; i < MROWS; ++i) xsum[i] = 0.f;
@@ -247,32 +365,16 @@ __global__ __launch_bounds__(1024) void stripe_kernel(const GemmArgs a, unsigned
         }
     }
 
-    // Sum over the waves in wave order: red[wave][m][column of the stripe].
-    __syncthreads();
-    float *red = reinterpret_cast<float *>(smem);
+    // Phase 3 inside the workgroup, then across workgroups.  The atomic finish wants consecutive lanes on
+    // consecutive outputs (one 8-byte atomic per lane: four cache lines per wave-wide instruction); the
+    // other finishes move four neighbouring outputs per lane.
+    RowSums<MROWS> sums;
 #pragma unroll
-    for (int i = 0; i < MROWS; ++i)
-        *reinterpret_cast<float4_t *>(red + ((size_t)(wave * MROWS + i) * kStripe + 4 * lane)) =
-            (float4_t){tot[0][i], tot[1][i], tot[2][i], tot[3][i]};
-    __syncthreads();
-    for (int o = tid; o < MROWS * kStripe; o += blockDim.x) {
-        const int m = o / kStripe, c = o - m * kStripe;
-        const int col = stripe * kStripe + c;
-        if (m >= a.M || col >= a.N) continue;
-        float v = red[m * kStripe + c];
-        for (int w = 1; w < waves; ++w) v += red[(size_t)(w * MROWS + m) * kStripe + c];
-        const size_t out = (size_t)m * a.N + col;
-        if (a.split == 1) {
-            a.Y[out] = (uint16_t)(pack_half2(v, 0.f) & 0xFFFFu);
-        } else {
-            const unsigned long long add = to_fixed(v);
-            const unsigned long long total = __hip_atomic_fetch_add(acc + out, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
-            if ((total >> 56) == (unsigned long long)a.split) {
-                a.Y[out] = (uint16_t)(pack_half2(from_fixed(total), 0.f) & 0xFFFFu);
-                __hip_atomic_store(acc + out, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-    }
+    for (int i = 0; i < MROWS; ++i) sums.r[i] = (float4_t){tot[0][i], tot[1][i], tot[2][i], tot[3][i]};
+    if (a.split > 1 && !a.partials)
+        reduce_and_finish<MROWS, 1>(a, acc, smem, sums, red_waves, stripe, slice);
+    else
+        reduce_and_finish<MROWS, 4>(a, acc, smem, sums, red_waves, stripe, slice);
 }
 
 __global__ __launch_bounds__(256) void clear_kernel(unsigned long long *p, size_t n)
@@ -281,13 +383,17 @@ __global__ __launch_bounds__(256) void clear_kernel(unsigned long long *p, size_
     if (i < n) p[i] = 0ull;
 }
 
-int mrows_of(int M) { return M == 1 ? 1 : (M == 2 ? 2 : 4); }
+int mrows_of(int M) { return M == 1 ? 1 : (M == 2 ? 2 : (M <= 4 ? 4 : (M <= 8 ? 8 : 16))); }
 
 template <int MROWS>
 hipError_t launch_m(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream)
 {
+    if (waves < Mma<MROWS>::kMinWaves || waves * 64 > Mma<MROWS>::kMaxThreads) return hipErrorInvalidValue;
     const size_t lds = stripe_lds_bytes(a.M, a.group, a.groups_per_split, waves);
     if (lds > (size_t)stripe_lds_limit()) return hipErrorInvalidValue;
+    int red_waves = (int)(lds / ((size_t)MROWS * kStripe * 4));  // >= 1 by stripe_lds_bytes
+    if (red_waves > waves) red_waves = waves;
+    if (red_waves > Mma<MROWS>::kRedWaves) red_waves = Mma<MROWS>::kRedWaves;
     const unsigned long long rows = (unsigned long long)a.groups_per_split * (a.group / 8);
     if (rows * a.N * 4ull >= 0x7F000000ull) return hipErrorInvalidValue;  // slice-relative 32-bit buffer offsets
     const int nstripes = (a.N + kStripe - 1) / kStripe;
@@ -296,19 +402,25 @@ hipError_t launch_m(const GemmArgs &a, unsigned long long *acc, int waves, hipSt
                                            hipFuncAttributeMaxDynamicSharedMemorySize, stripe_lds_limit());
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((stripe_kernel<MROWS>), dim3(nstripes * a.split), dim3(waves * 64), lds, stream, a, acc);
+    hipLaunchKernelGGL((stripe_kernel<MROWS>), dim3(nstripes * a.split), dim3(waves * 64), lds, stream, a, acc, red_waves);
     return hipGetLastError();
 }
 
 }  // namespace
 
 int stripe_lds_limit() { return kLdsLimit; }
+int stripe_min_waves(int M) { return M > 4 ? 4 : 1; }
+int stripe_max_waves(int M) { return M > 4 ? 8 : 16; }
 
+// Staged X and block sums; the final sums reuse the space, at least one wave's worth of them
+// (more waves per round when there is room: fewer barriers).
 size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves)
 {
     const int mrows = mrows_of(M);
     const size_t stage = lds_map(mrows, groups_per_split * (group / 8)).total;
-    const size_t red = (size_t)waves * mrows * kStripe * 4;
+    const size_t one = (size_t)mrows * kStripe * 4;
+    size_t red = one * waves;
+    if (red > 64 * 1024) red = 64 * 1024 < one ? one : 64 * 1024 / one * one;
     return stage > red ? stage : red;
 }
 
@@ -318,13 +430,22 @@ hipError_t launch_stripe_clear(unsigned long long *acc, size_t n, hipStream_t st
     return hipGetLastError();
 }
 
+// `acc` != null: the slices meet in the fixed-point accumulator; else a.partials (FP32 [S, M, N]) takes them
+// and the caller runs the second pass.  Neither is used when a.split == 1.
 hipError_t launch_stripe(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream)
 {
-    if (a.M > 4 || waves < 1 || waves > 16 || a.group % (8 * kBlockRows) != 0) return hipErrorInvalidValue;
-    if (a.split > 1 && (!acc || a.split > 255)) return hipErrorInvalidValue;
-    if (a.M == 1) return launch_m<1>(a, acc, waves, stream);
-    if (a.M == 2) return launch_m<2>(a, acc, waves, stream);
-    return launch_m<4>(a, acc, waves, stream);
+    if (a.M > 16 || a.group % (8 * kBlockRows) != 0) return hipErrorInvalidValue;
+    if (a.split > 1 && !acc && !a.partials) return hipErrorInvalidValue;
+    if (a.split > 1 && acc && a.split > 255) return hipErrorInvalidValue;
+    GemmArgs b = a;
+    if (acc || a.split == 1) b.partials = nullptr;  // the kernel reads the finish mode off this pointer
+    switch (mrows_of(a.M)) {
+    case 1: return launch_m<1>(b, acc, waves, stream);
+    case 2: return launch_m<2>(b, acc, waves, stream);
+    case 4: return launch_m<4>(b, acc, waves, stream);
+    case 8: return launch_m<8>(b, acc, waves, stream);
+    default: return launch_m<16>(b, acc, waves, stream);
+    }
 }
 
 }  // namespace w4a16

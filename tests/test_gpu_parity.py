@@ -78,7 +78,7 @@ def test_small_shapes_every_split(gpu, M, K, N, group):
     ref = orc.gemm(X, Wp, s, Zp, group)
     G = K // group
     kernels = [binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS] + (
-        [binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE] if M <= 4 else [])
+        [binding.KERNEL_WAVE_SPLIT] if M <= 4 else []) + ([binding.KERNEL_STRIPE] if M <= 16 else [])
     for kernel in kernels:
         for split in sorted({0, 1, 2, 3, G}):
             if split > G:

@@ -62,6 +62,8 @@ def test_argument_checks_need_no_gpu(binding):
     with pytest.raises(binding.W4A16Error):
         binding.query_plan(1, 64, 256, 128, split=3)  # only two groups
     with pytest.raises(binding.W4A16Error):
+        binding.query_plan(17, 64, 256, 128, kernel=binding.KERNEL_STRIPE)  # that family is for M <= 16
+    with pytest.raises(binding.W4A16Error):
         binding.query_plan(1, 64, 256, 128, kernel=4)
 
 
@@ -74,7 +76,7 @@ SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336),
 def test_plans_are_well_formed(binding, M, N, K):
     G = K // 128
     for kernel in (binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS) + (
-            (binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE) if M <= 4 else ()):
+            (binding.KERNEL_WAVE_SPLIT,) if M <= 4 else ()) + ((binding.KERNEL_STRIPE,) if M <= 16 else ()):
         for split in sorted({0, 1, 2, 7, G}):
             if split > G:
                 continue
@@ -85,13 +87,15 @@ def test_plans_are_well_formed(binding, M, N, K):
             if split:
                 assert S <= split
             stripe = p["kernel"] == binding.KERNEL_STRIPE
-            assert p["workspace_bytes"] == ((M * N * 8 if stripe else S * M * N * 4) if S > 1 else 0)
-            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (3 if M <= 4 else (1 if M <= 16 else 2)))
+            in_acc = stripe and S <= 255 and S * M * N <= 320 * 1024  # slices meet in the 64-bit accumulator
+            assert p["workspace_bytes"] == ((M * N * 8 if in_acc else S * M * N * 4) if S > 1 else 0)
+            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (3 if M <= 16 else 2))
             tiles_n = -(-N // p["tile_n"])
             tiles_m = -(-M // p["tile_m"]) if p["kernel"] not in (binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE) else 1
             assert p["workgroups"] == tiles_n * tiles_m * S
             if stripe:
-                assert S <= 255 and 1 <= p["waves_k"] <= 16 and p["threads"] == 64 * p["waves_k"] and p["tile_n"] == 256
+                assert (1 if M <= 4 else 4) <= p["waves_k"] <= (16 if M <= 4 else 8)
+                assert p["threads"] == 64 * p["waves_k"] and p["tile_n"] == 256
             else:
                 assert p["threads"] in (256, 1024) and p["waves_k"] in (1, 16)
     assert binding.workspace_bytes(M, N, K, 128) >= binding.query_plan(M, N, K, 128)["workspace_bytes"]
