@@ -92,11 +92,17 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 //   that each unpacked weight word feeds 2 or 4 MFMAs and W is read once per 32
 //   or 64 rows.
 // How the K slices of different workgroups of a STRIPE plan meet: in the 64-bit fixed-point accumulator (one
-// returning atomic add per output and slice; the GPU retires ~150 of them per ns-thousand, measured) while
-// that is cheaper than a second launch, else in the FP32 workspace and the second pass.
+// returning atomic add per output and slice; measured: the GPU retires about 150 of them per nanosecond)
+// while that is cheaper than a second launch (about 3.3 us, measured), else in the FP32 workspace and the
+// second pass.  Measured crossover: between 0.5 M and 1 M adds.
 bool stripe_meets_in_accumulator(int M, int N, int S)
 {
-    return S <= 255 && (long long)S * M * N <= 320 * 1024;
+    if (S > 255) return false;
+    if (const char *e = getenv("W4A16_STRIPE_FINISH")) {  // tuning aid for sweeps, not part of the contract
+        if (e[0] == 'a') return true;
+        if (e[0] == 'w') return false;
+    }
+    return (long long)S * M * N <= 640 * 1024;
 }
 
 int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4a16_plan *p)

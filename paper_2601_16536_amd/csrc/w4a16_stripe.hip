@@ -38,11 +38,12 @@
 //
 // The MFMA sums P = 2^-24 sum_k x_k q_k run over all of a wave's rows of one
 // quantisation group before scale and zero point are applied (Eq. 2, in fp32).
-// X (as A-operand entries) and the sums of x per block are staged in LDS once,
-// behind one barrier.  Scales and zero points travel with the weight blocks
-// (one 8-byte and one 4-byte load per block, mostly cache hits): staging them
-// in LDS ahead of the loop instead was measured 1 us slower, because the waves
-// then sit at the barrier on cold loads with only their first blocks in flight.
+// X reaches the MFMA through LDS, staged by each wave for its own run of rows in
+// double-buffered chunks (no workgroup barrier before the final sum; staging the
+// whole slice behind one barrier was measured 1 to 4 us slower, growing with M).
+// Scales and zero points travel with the weight blocks (one 8-byte and one
+// 4-byte load per block, mostly cache hits): staging them in LDS ahead of the
+// loop instead was measured 1 us slower.
 #include "w4a16_device.h"
 #include "w4a16_internal.h"
 #include <type_traits>
@@ -53,22 +54,21 @@ namespace {
 constexpr int kStripe = 256;    // columns per workgroup: 64 lanes x 4 words
 constexpr int kBlockRows = 2;   // packed rows per block (16 k)
 constexpr int kRing = 2;        // blocks in flight per wave
-constexpr int kStageBatch = 4;  // 16-byte entries of X a thread requests at a time beyond the first ones
 constexpr int kLdsLimit = 144 * 1024;
 
-// LDS map of one workgroup (bytes), for `rows` packed rows.
-struct LdsMap {
-    size_t xs, zero, bs, total;
+// X reaches the MFMA through LDS in chunks that each wave stages for itself (a wave only needs the X of
+// its own run of rows, so no workgroup barrier is involved): kChunkRows packed rows at a time, double
+// buffered.  A chunk holds 64 (M <= 8) or 128 (M = 16) A-operand entries of 16 bytes and the fp32 sums
+// of x per block and row of X; one more entry per wave is all zero.
+template <int MROWS>
+struct Chunk {
+    static constexpr int kRows = MROWS >= 8 ? 8 : 64 / MROWS;        // packed rows per chunk
+    static constexpr int kBlocks = kRows / kBlockRows;
+    static constexpr int kEntries = kRows * MROWS;                    // 16-byte entries per chunk
+    static constexpr int kPerLane = kEntries / 64;
+    static constexpr int kBufBytes = kEntries * 16 + kBlocks * MROWS * 4;
+    static constexpr int kWaveBytes = 2 * kBufBytes + 16;             // two buffers and the zero entry
 };
-__host__ __device__ inline LdsMap lds_map(int mrows, int rows)
-{
-    LdsMap m;
-    m.xs = 0;                                                  // [rows][mrows] A-operand entries of 16 bytes
-    m.zero = (size_t)rows * mrows * 16;                        // one all-zero entry
-    m.bs = m.zero + 16;                                        // [rows / kBlockRows][mrows] fp32 sums of x
-    m.total = m.bs + (size_t)(rows / kBlockRows) * mrows * 4;
-    return m;
-}
 
 // Fixed-point form of a slice sum for the cross-workgroup accumulator: the value
 // in units of 2^-24 (clamped far outside the FP16 range), biased to be positive,
@@ -102,7 +102,6 @@ struct Mma {
     static constexpr int kMaxThreads = wide ? 512 : 1024;  // the wide form needs up to 256 registers per lane
     static constexpr int kMinWaves = wide ? 4 : 1;
     static constexpr int kRedWaves = wide ? 64 / MROWS : 16;         // waves per round of the final sum, at most
-    static constexpr int kPre = wide ? MROWS : 2;                    // entries of X a thread requests ahead of the weights
 };
 
 // Sum of the waves' results in wave order, `red_waves` waves per round through LDS
@@ -231,40 +230,42 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
         for (int t = 0; t < kBlockRows; ++t)
             r.w[t] = __builtin_amdgcn_raw_buffer_load_b128(rw, valid ? vw : kOutOfRange, base + (uint32_t)t * row_w, 2);
     };
-    // ---- stage X and its block sums ----
-    const LdsMap lm = lds_map(MROWS, rows);
-    uint4_t *xs = reinterpret_cast<uint4_t *>(smem + lm.xs);
-    float *bs = reinterpret_cast<float *>(smem + lm.bs);
-    // X goes first: loads return in order, and X (mostly cache hits) must not queue behind the first
-    // weight blocks, which come from DRAM.  kPre entries per thread are requested ahead of the weights
-    // (all of the slice's X at the tuned shapes); what is left follows behind them.
-    const int nthreads = blockDim.x;
-    const int total = rows * MROWS;  // a multiple of 2 MROWS: lanes (idx, idx ^ MROWS) hold one block of one row of X
-    // Entry idx = packed row idx / MROWS of X row idx % MROWS: consecutive lanes write consecutive LDS
-    // entries (no bank conflicts) and still read whole cache lines of X (64 / MROWS neighbouring rows' worth).
-    auto x_load = [&](int idx) {
-        const int m = idx & (MROWS - 1), kb = idx / MROWS;
-        uint4_t d = {0u, 0u, 0u, 0u};
-        if (idx < total && m < a.M) d = *reinterpret_cast<const uint4_t *>(a.X + (size_t)m * a.K + (size_t)(row_base + kb) * 8);
-        return d;
-    };
-    auto x_store = [&](int idx, uint4_t d) {
-        const int m = idx & (MROWS - 1), kb = idx / MROWS;
-        float sum = sum8(d);
-        sum += __shfl_xor(sum, MROWS, 64);  // the other packed row of the block, same row of X
-        if (idx < total) {
-            xs[idx] = permute_x(d);
-            if ((kb & 1) == 0) bs[(kb >> 1) * MROWS + m] = sum;
+    // ---- X: this wave's LDS, chunk loader and chunk writer ----
+    typedef Chunk<MROWS> Ch;
+    unsigned char *wl = smem + (size_t)wave * Ch::kWaveBytes;  // buffer 0, buffer 1, zero entry
+    const uint32_t zero_off = (uint32_t)(wave * Ch::kWaveBytes + 2 * Ch::kBufBytes);
+    // X as a buffer: rows past the wave's run (or past M) are read through an out-of-range offset, so that
+    // every chunk issues the same number of loads (exact wait counts) and the missing entries are zero.
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(a.X), 0, (uint32_t)((size_t)a.M * a.K * 2), kRawBuffer);
+    const uint32_t row_end = (uint32_t)row_base + wb1 * kBlockRows;  // first packed row (of K) past the wave's run
+    // entry e of a chunk = packed row e / MROWS of X row e % MROWS: consecutive lanes write consecutive LDS
+    // entries (no bank conflicts) and read 64 / MROWS neighbouring rows' worth of each row of X
+    auto x_load = [&](uint4_t(&d)[Ch::kPerLane], uint32_t first_block) {
+#pragma unroll
+        for (int q = 0; q < Ch::kPerLane; ++q) {
+            const uint32_t e = (uint32_t)lane + 64u * q, m = e & (MROWS - 1), kr = (uint32_t)row_base + first_block * kBlockRows + e / MROWS;
+            const bool valid = kr < row_end && m < (uint32_t)a.M;
+            d[q] = __builtin_amdgcn_raw_buffer_load_b128(rx, valid ? (m * (uint32_t)a.K + kr * 8u) * 2u : kOutOfRange, 0, 0);
         }
     };
-    constexpr int kPre = Mma<MROWS>::kPre;
-    uint4_t pre[kPre];
+    auto x_store = [&](const uint4_t(&d)[Ch::kPerLane], int par) {
+        uint4_t *xs = reinterpret_cast<uint4_t *>(wl + par * Ch::kBufBytes);
+        float *bs = reinterpret_cast<float *>(wl + par * Ch::kBufBytes + Ch::kEntries * 16);
 #pragma unroll
-    for (int it = 0; it < kPre; ++it) {
-        pre[it] = (uint4_t){0u, 0u, 0u, 0u};
-        if (it * nthreads + wave * 64 < total) pre[it] = x_load(it * nthreads + tid);  // wave-uniform condition
-    }
+        for (int q = 0; q < Ch::kPerLane; ++q) {
+            const int e = lane + 64 * q, m = e & (MROWS - 1), kl = e / MROWS;
+            float sum = sum8(d[q]);
+            sum += __shfl_xor(sum, MROWS, 64);  // the other packed row of the block, same row of X
+            xs[e] = permute_x(d[q]);
+            if ((kl & 1) == 0) bs[(kl >> 1) * MROWS + m] = sum;
+        }
+    };
 
+    // X of the first chunk goes ahead of the weights: loads return in order, and X (mostly cache hits) must
+    // not queue behind the first weight blocks, which come from DRAM.
+    uint4_t xd[Ch::kPerLane];
+    x_load(xd, wb0);
     // (lg, lnext): group of the next block to load and the first block of the group after it
     uint32_t lg = wb0 / bpg, lnext = (lg + 1) * bpg;
 #pragma unroll
@@ -272,21 +273,10 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
         load_block(buf[p], wb0 + p, lg);
         if (wb0 + p + 1 == lnext) { ++lg; lnext += bpg; }
     }
+    if (lane == 0) *reinterpret_cast<uint4_t *>(smem + zero_off) = (uint4_t){0u, 0u, 0u, 0u};
+    x_store(xd, 0);
 
-#pragma unroll
-    for (int it = 0; it < kPre; ++it)
-        if (it * nthreads + wave * 64 < total) x_store(it * nthreads + tid, pre[it]);
-    for (int base = kPre * nthreads; base < total; base += kStageBatch * nthreads) {  // long slices only
-        uint4_t d[kStageBatch];
-#pragma unroll
-        for (int it = 0; it < kStageBatch; ++it) d[it] = x_load(base + it * nthreads + tid);
-#pragma unroll
-        for (int it = 0; it < kStageBatch; ++it) x_store(base + it * nthreads + tid, d[it]);
-    }
-    if (tid == 0) *reinterpret_cast<uint4_t *>(smem + lm.zero) = (uint4_t){0u, 0u, 0u, 0u};
-    __syncthreads();
-
-    // this lane's A-operand entry of packed row 0: a row of X, or the zero entry
+    // this lane's A-operand entry of packed row 0 of a chunk: a row of X, or the zero entry
     int r;
     bool has_row;
     if constexpr (Mma<MROWS>::wide) {
@@ -298,9 +288,10 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
         r = j - 4 * g4;                                     // row 4g + r holds X row r for k-group g only
         has_row = r >= 0 && r < MROWS;
     }
-    const uint32_t xa0 = has_row ? (uint32_t)(lm.xs + r * 16) : (uint32_t)lm.zero;
-    const uint32_t xstep = has_row ? (uint32_t)(MROWS * 16) : 0u;  // bytes per packed row
-    const uint32_t zsh = (uint32_t)(col0 & 7) * 4u;                // this lane's four nibbles in its zero-point word
+    const uint32_t xa0 = has_row ? (uint32_t)(wave * Ch::kWaveBytes + r * 16) : zero_off;  // in buffer 0
+    const uint32_t xstep = has_row ? (uint32_t)(MROWS * 16) : 0u;                          // bytes per packed row
+    const uint32_t xpar = has_row ? (uint32_t)Ch::kBufBytes : 0u;                          // buffer 1 - buffer 0
+    const uint32_t zsh = (uint32_t)(col0 & 7) * 4u;  // this lane's four nibbles in its zero-point word
 
     float tot[4][MROWS];
 #pragma unroll
@@ -318,51 +309,63 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
 
     uint32_t gnext = (wb0 / bpg + 1) * bpg;  // first block of the group after the current one
 
-    for (uint32_t b = wb0; b < wb1; b += kRing) {
+    // Only this wave touches its LDS and the LDS operations of one wave complete in order; the
+    // fences only keep the compiler from moving them across the staging.
+    int par = 0;
+    for (uint32_t cb = wb0; cb < wb1; cb += Ch::kBlocks, par ^= 1) {
+        x_load(xd, cb + Ch::kBlocks);  // the next chunk's X (nothing past the wave's run)
+        const uint32_t xa = xa0 + (uint32_t)par * xpar;
+        const float *bs = reinterpret_cast<const float *>(wl + par * Ch::kBufBytes + Ch::kEntries * 16);
+        const uint32_t nb = wb1 - cb < (uint32_t)Ch::kBlocks ? wb1 - cb : (uint32_t)Ch::kBlocks;  // blocks of this chunk
+        for (uint32_t bb = 0; bb < nb; bb += kRing) {
 #pragma unroll
-        for (int p = 0; p < kRing; ++p) {
-            const uint32_t cur = b + p;
-            if (cur < wb1) {
-                // Loads return in order and the block's scales and zero points were issued ahead of its
-                // weights.  Naming them here, used or not, tells the compiler that they have landed, so that
-                // reloading their registers below needs no wait on younger loads.
-                asm volatile("" ::"v"(buf[p].sc[0]), "v"(buf[p].sc[1]), "v"(buf[p].zw));
+            for (int p = 0; p < kRing; ++p) {
+                const uint32_t lb = bb + p, cur = cb + lb;  // block of the chunk, block of the slice
+                if (cur < wb1) {
+                    // Loads return in order and the block's scales and zero points were issued ahead of its
+                    // weights.  Naming them here, used or not, tells the compiler that they have landed, so
+                    // that reloading their registers below needs no wait on younger loads.
+                    asm volatile("" ::"v"(buf[p].sc[0]), "v"(buf[p].sc[1]), "v"(buf[p].zw));
 #pragma unroll
-                for (int t = 0; t < kBlockRows; ++t) {
-                    H8 x;
-                    x.u = *reinterpret_cast<const uint4_t *>(smem + xa0 + (cur * kBlockRows + t) * xstep);
+                    for (int t = 0; t < kBlockRows; ++t) {
+                        H8 x;
+                        x.u = *reinterpret_cast<const uint4_t *>(smem + xa + (lb * kBlockRows + t) * xstep);
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        if constexpr (Mma<MROWS>::wide)
-                            part[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x.h, unpack8(buf[p].w[t][c], masks), part[c], 0, 0, 0);
-                        else
-                            part[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, unpack8(buf[p].w[t][c], masks), part[c], 0, 0, 0);
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < MROWS; ++i) xsum[i] += bs[cur * MROWS + i];
-                if (cur + 1 == gnext || cur + 1 == wb1) {
-                    // the wave's rows of this group are done: scale and zero point (Eq. 2)
-                    H2 s01, s23;
-                    s01.u = buf[p].sc[0];
-                    s23.u = buf[p].sc[1];
-                    const float s[4] = {(float)s01.h[0], (float)s01.h[1], (float)s23.h[0], (float)s23.h[1]};
-                    const uint32_t zw = buf[p].zw >> zsh;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const float z = (float)((zw >> (4 * c)) & 15u);
-#pragma unroll
-                        for (int i = 0; i < MROWS; ++i) tot[c][i] = apply_scale_zero(tot[c][i], s[c], z, part[c][i], xsum[i]);
-                        part[c] = Acc(0.f);
+                        for (int c = 0; c < 4; ++c) {
+                            if constexpr (Mma<MROWS>::wide)
+                                part[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x.h, unpack8(buf[p].w[t][c], masks), part[c], 0, 0, 0);
+                            else
+                                part[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, unpack8(buf[p].w[t][c], masks), part[c], 0, 0, 0);
+                        }
                     }
 #pragma unroll
-                    for (int i = 0; i < MROWS; ++i) xsum[i] = 0.f;
-                    gnext += bpg;
+                    for (int i = 0; i < MROWS; ++i) xsum[i] += bs[lb * MROWS + i];
+                    if (cur + 1 == gnext || cur + 1 == wb1) {
+                        // the wave's rows of this group are done: scale and zero point (Eq. 2)
+                        H2 s01, s23;
+                        s01.u = buf[p].sc[0];
+                        s23.u = buf[p].sc[1];
+                        const float s[4] = {(float)s01.h[0], (float)s01.h[1], (float)s23.h[0], (float)s23.h[1]};
+                        const uint32_t zw = buf[p].zw >> zsh;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const float z = (float)((zw >> (4 * c)) & 15u);
+#pragma unroll
+                            for (int i = 0; i < MROWS; ++i) tot[c][i] = apply_scale_zero(tot[c][i], s[c], z, part[c][i], xsum[i]);
+                            part[c] = Acc(0.f);
+                        }
+#pragma unroll
+                        for (int i = 0; i < MROWS; ++i) xsum[i] = 0.f;
+                        gnext += bpg;
+                    }
                 }
+                load_block(buf[p], cur + kRing, lg);
+                if (cur + kRing + 1 == lnext) { ++lg; lnext += bpg; }
             }
-            load_block(buf[p], cur + kRing, lg);
-            if (cur + kRing + 1 == lnext) { ++lg; lnext += bpg; }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        x_store(xd, par ^ 1);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
 
     // Phase 3 inside the workgroup, then across workgroups.  The atomic finish wants consecutive lanes on
@@ -412,12 +415,22 @@ int stripe_lds_limit() { return kLdsLimit; }
 int stripe_min_waves(int M) { return M > 4 ? 4 : 1; }
 int stripe_max_waves(int M) { return M > 4 ? 8 : 16; }
 
-// Staged X and block sums; the final sums reuse the space, at least one wave's worth of them
-// (more waves per round when there is room: fewer barriers).
+// The waves' chunk buffers; the final sums reuse the space, at least one wave's worth of them (more waves
+// per round when there is room: fewer barriers).
 size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves)
 {
+    (void)group;
+    (void)groups_per_split;
     const int mrows = mrows_of(M);
-    const size_t stage = lds_map(mrows, groups_per_split * (group / 8)).total;
+    size_t stage = 0;
+    switch (mrows) {
+    case 1: stage = Chunk<1>::kWaveBytes; break;
+    case 2: stage = Chunk<2>::kWaveBytes; break;
+    case 4: stage = Chunk<4>::kWaveBytes; break;
+    case 8: stage = Chunk<8>::kWaveBytes; break;
+    default: stage = Chunk<16>::kWaveBytes; break;
+    }
+    stage *= waves;
     const size_t one = (size_t)mrows * kStripe * 4;
     size_t red = one * waves;
     if (red > 64 * 1024) red = 64 * 1024 < one ? one : 64 * 1024 / one * one;

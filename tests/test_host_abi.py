@@ -87,7 +87,7 @@ def test_plans_are_well_formed(binding, M, N, K):
             if split:
                 assert S <= split
             stripe = p["kernel"] == binding.KERNEL_STRIPE
-            in_acc = stripe and S <= 255 and S * M * N <= 320 * 1024  # slices meet in the 64-bit accumulator
+            in_acc = stripe and S <= 255 and S * M * N <= 640 * 1024  # slices meet in the 64-bit accumulator
             assert p["workspace_bytes"] == ((M * N * 8 if in_acc else S * M * N * 4) if S > 1 else 0)
             assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (3 if M <= 16 else 2))
             tiles_n = -(-N // p["tile_n"])
