@@ -75,9 +75,11 @@ typedef enum {
     W4A16_KERNEL_MFMA_REG = 1,   /* any M: 256-column tiles, weights unpacked straight into MFMA operand registers */
     W4A16_KERNEL_MFMA_ROWS = 2,  /* any M, meant for M > 16: as MFMA_REG with 32 or 64 rows of X staged in LDS per
                                     workgroup, every unpacked weight word reused over the row tiles               */
-    W4A16_KERNEL_STRIPE = 3      /* M <= 4: 256-column stripe x K slice per workgroup, its waves own contiguous runs
+    W4A16_KERNEL_STRIPE = 3,     /* M <= 16: 256-column stripe x K slice per workgroup, its waves own contiguous runs
                                     of the slice (LDS reduction); slices of different workgroups meet in a 64-bit
                                     fixed-point accumulator by one atomic add each, no second launch              */
+    W4A16_KERNEL_TILE = 4        /* any M, meant for M >= 17: 64-column tile x 16, 32 or 64 rows of X per workgroup,
+                                    its waves own contiguous runs of K (LDS reduction), plain MFMA operand layout  */
 } w4a16_kernel;
 
 /* What the scheduler decided for a shape (Algorithm 1 takes S and the block

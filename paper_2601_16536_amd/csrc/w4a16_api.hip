@@ -109,9 +109,9 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
 {
     const int G = K / group;
     if (kernel == W4A16_KERNEL_AUTO)
-        kernel = M <= 16 ? W4A16_KERNEL_STRIPE : W4A16_KERNEL_MFMA_ROWS;
+        kernel = M <= 16 ? W4A16_KERNEL_STRIPE : W4A16_KERNEL_TILE;
     if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG && kernel != W4A16_KERNEL_MFMA_ROWS &&
-        kernel != W4A16_KERNEL_STRIPE)
+        kernel != W4A16_KERNEL_STRIPE && kernel != W4A16_KERNEL_TILE)
         return W4A16_ERR_UNSUPPORTED;
     if (kernel == W4A16_KERNEL_WAVE_SPLIT && M > 4) return W4A16_ERR_UNSUPPORTED;
     if (kernel == W4A16_KERNEL_STRIPE && M > 16) return W4A16_ERR_UNSUPPORTED;
@@ -153,6 +153,30 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->workspace_bytes = S == 1 ? 0
                              : stripe_meets_in_accumulator(M, N, S) ? (size_t)M * N * sizeof(unsigned long long)
                                                                     : (size_t)S * M * N * sizeof(float);
+        return W4A16_OK;
+    }
+    if (kernel == W4A16_KERNEL_TILE) {
+        p->tile_n = 64;
+        p->waves_k = 8;
+        p->threads = 512;
+        tiles = (N + 63) / 64;
+        // Rows of X per workgroup: as many (16, 32 or 64: each loaded weight word feeds that many MFMA rows)
+        // as still leave one workgroup per compute unit without splitting K across workgroups (a split costs
+        // the FP32 partials and the second pass).
+        int rows_x = 64;
+        while (rows_x > 16 && (rows_x / 2 >= M || tiles * ((M + rows_x - 1) / rows_x) < cus)) rows_x /= 2;
+        p->tile_m = rows_x;
+        const long long wgs = tiles * ((M + rows_x - 1) / rows_x);
+        if (S == 0) S = (int)((cus + wgs / 2) / wgs);
+        if (S < 1) S = 1;
+        if (S > G) S = G;
+        int gps = (G + S - 1) / S;
+        while (gps > 1 && (unsigned long long)gps * (group / 8) * N * 4ull >= 0x7F000000ull) gps = (gps + 1) / 2;
+        S = (G + gps - 1) / gps;
+        p->split = S;
+        p->groups_per_split = gps;
+        p->workgroups = (int)(wgs * S);
+        p->workspace_bytes = S > 1 ? (size_t)S * M * N * sizeof(float) : 0;
         return W4A16_OK;
     }
     if (kernel == W4A16_KERNEL_WAVE_SPLIT) {
@@ -300,6 +324,7 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
 
     hipError_t e = plan.kernel == W4A16_KERNEL_STRIPE
                        ? launch_stripe(a, in_acc ? static_cast<unsigned long long *>(ws) : nullptr, plan.waves_k, st)
+                   : plan.kernel == W4A16_KERNEL_TILE       ? launch_tile(a, plan.tile_m, plan.waves_k, st)
                    : plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st)
                    : plan.kernel == W4A16_KERNEL_MFMA_ROWS  ? launch_mfma_rows(a, plan.tile_m, st)
                                                             : launch_mfma_reg(a, st);

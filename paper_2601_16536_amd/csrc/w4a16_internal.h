@@ -39,6 +39,10 @@ size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves);  // 
 int stripe_lds_limit();                                                       // most it may use
 int stripe_min_waves(int M);
 int stripe_max_waves(int M);
+// TILE family (meant for M >= 17): 64-column tiles, `rows_x` (16, 32 or 64) rows of X per workgroup,
+// `waves` (4..8) waves per workgroup that split the K slice; split > 1 puts the slices in a.partials.
+hipError_t launch_tile(const GemmArgs &a, int rows_x, int waves, hipStream_t stream);
+size_t tile_lds_bytes(int rows_x, int waves);
 // Second pass (Algorithm 1, Phase 3).
 hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream);
 

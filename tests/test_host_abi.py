@@ -64,7 +64,7 @@ def test_argument_checks_need_no_gpu(binding):
     with pytest.raises(binding.W4A16Error):
         binding.query_plan(17, 64, 256, 128, kernel=binding.KERNEL_STRIPE)  # that family is for M <= 16
     with pytest.raises(binding.W4A16Error):
-        binding.query_plan(1, 64, 256, 128, kernel=4)
+        binding.query_plan(1, 64, 256, 128, kernel=5)
 
 
 SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336), (16, 4096, 14336), (1, 8192, 28672),
@@ -75,7 +75,7 @@ SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336),
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_plans_are_well_formed(binding, M, N, K):
     G = K // 128
-    for kernel in (binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS) + (
+    for kernel in (binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS, binding.KERNEL_TILE) + (
             (binding.KERNEL_WAVE_SPLIT,) if M <= 4 else ()) + ((binding.KERNEL_STRIPE,) if M <= 16 else ()):
         for split in sorted({0, 1, 2, 7, G}):
             if split > G:
@@ -89,13 +89,15 @@ def test_plans_are_well_formed(binding, M, N, K):
             stripe = p["kernel"] == binding.KERNEL_STRIPE
             in_acc = stripe and S <= 255 and S * M * N <= 640 * 1024  # slices meet in the 64-bit accumulator
             assert p["workspace_bytes"] == ((M * N * 8 if in_acc else S * M * N * 4) if S > 1 else 0)
-            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (3 if M <= 16 else 2))
+            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (3 if M <= 16 else 4))
             tiles_n = -(-N // p["tile_n"])
             tiles_m = -(-M // p["tile_m"]) if p["kernel"] not in (binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE) else 1
             assert p["workgroups"] == tiles_n * tiles_m * S
             if stripe:
                 assert (1 if M <= 4 else 4) <= p["waves_k"] <= (16 if M <= 4 else 8)
                 assert p["threads"] == 64 * p["waves_k"] and p["tile_n"] == 256
+            elif p["kernel"] == binding.KERNEL_TILE:
+                assert p["threads"] == 512 and p["waves_k"] == 8 and p["tile_n"] == 64 and p["tile_m"] in (16, 32, 64)
             else:
                 assert p["threads"] in (256, 1024) and p["waves_k"] in (1, 16)
     assert binding.workspace_bytes(M, N, K, 128) >= binding.query_plan(M, N, K, 128)["workspace_bytes"]
