@@ -31,8 +31,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 MFMA rate
 COLD_BYTES = 640 * 1024 * 1024
 # HBM bytes per launch of the headline kernel, from the committed rocprofv3 --pmc summaries
-# (profiles/hbm_traffic_c4_m1.json: FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size).
+# (profiles/hbm_traffic.json: FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size).
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+KERNEL_NAMES = {0: "wave_split_kernel", 1: "mfma_reg_kernel", 2: "mfma_rows_kernel", 3: "stripe_kernel", 4: "tile_kernel"}
 
 
 def measured_traffic(key):
@@ -181,7 +182,9 @@ def main():
         "achieved_TBps": res["GBps"] * 1e-3, "achieved_TFLOPs": res["TFLOPs"],
         "roofline": {"bound": "hbm", "achieved": res["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": res["hbm_frac"], "traffic": measured_traffic("%s_M%d" % (args.config, args.M)),
-                     "kernel": "wave_split_kernel" if res["plan"]["kernel"] == 0 else "mfma_reg_kernel",
+                     "launches_per_step": 1 if res["plan"]["split"] == 1 or res["plan"]["workspace_bytes"] ==
+                     8 * args.M * cfg.N else 2,
+                     "kernel": KERNEL_NAMES.get(res["plan"]["kernel"], "?"),
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"]},
         "cpu_baseline": cpu,
     }
