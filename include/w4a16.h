@@ -11,7 +11,7 @@
  * is how the library fills the GPU when N is small next to K: K is cut into S
  * slices on group boundaries; slices held by the waves of one workgroup meet in
  * LDS; slices held by different workgroups either add their sums into a 64-bit
- * fixed-point accumulator whose last arriver casts to FP16 (M <= 4), or put FP32
+ * fixed-point accumulator whose last arriver casts to FP16 (while the adds are few), or put FP32
  * partial results in a workspace that a second pass adds in a fixed order and
  * casts to FP16.
  * Unlike Algorithm 1 (Phase 1) the dequantized weights never travel through
@@ -75,11 +75,12 @@ typedef enum {
     W4A16_KERNEL_MFMA_REG = 1,   /* any M: 256-column tiles, weights unpacked straight into MFMA operand registers */
     W4A16_KERNEL_MFMA_ROWS = 2,  /* any M, meant for M > 16: as MFMA_REG with 32 or 64 rows of X staged in LDS per
                                     workgroup, every unpacked weight word reused over the row tiles               */
-    W4A16_KERNEL_STRIPE = 3,     /* M <= 16: 256-column stripe x K slice per workgroup, its waves own contiguous runs
+    W4A16_KERNEL_STRIPE = 3,     /* M <= 16, the scheduler's choice for M <= 4: 256-column stripe x K slice per workgroup, its waves own contiguous runs
                                     of the slice (LDS reduction); slices of different workgroups meet in a 64-bit
                                     fixed-point accumulator by one atomic add each, no second launch              */
-    W4A16_KERNEL_TILE = 4        /* any M, meant for M >= 17: 64-column tile x 16, 32 or 64 rows of X per workgroup,
-                                    its waves own contiguous runs of K (LDS reduction), plain MFMA operand layout  */
+    W4A16_KERNEL_TILE = 4        /* any M, the scheduler's choice for M >= 5: 64-column tile x 16, 32 or 64 rows of X
+                                    per workgroup, its waves own contiguous runs of K (LDS reduction), plain MFMA
+                                    operand layout; slices of different workgroups meet as in STRIPE                */
 } w4a16_kernel;
 
 /* What the scheduler decided for a shape (Algorithm 1 takes S and the block
@@ -93,7 +94,7 @@ typedef struct {
     int waves_k;           /* K slices inside a workgroup (waves whose results meet in LDS)   */
     int workgroups;        /* workgroups of the multiply launch                               */
     int threads;           /* threads per workgroup                                           */
-    size_t workspace_bytes;/* FP32 partials [S, M, N] (STRIPE: 64-bit sums [M, N]); 0 when S == 1 */
+    size_t workspace_bytes;/* 64-bit sums [M, N] or FP32 partials [S, M, N]; 0 when S == 1       */
 } w4a16_plan;
 
 /*
@@ -116,7 +117,7 @@ int w4a16_gemm_ex(const void *X, const uint32_t *Wpacked, const void *scales, co
  * The same, with the Split-K workspace brought by the caller: `workspace` is
  * device memory of at least the plan's workspace_bytes (w4a16_query_plan; for
  * the scheduler's own choice also w4a16_workspace_bytes), 256-byte aligned.
- * Its contents need no initialisation (for a STRIPE plan the library clears it
+ * Its contents need no initialisation (a plan that uses it as accumulator clears it
  * with one small extra launch first).  Performs no allocation.
  */
 int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,

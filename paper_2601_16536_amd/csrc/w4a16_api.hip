@@ -74,28 +74,33 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 // ---- the Split-K scheduler ---------------------------------------------------
 //
-// Algorithm 1 takes the split factor S and the block sizes as inputs.  Here:
+// Algorithm 1 takes the split factor S and the block sizes as inputs.  Here the
+// scheduler (kernel = AUTO, split = 0) chooses them from the shape alone:
 //
-// M <= 4 (WAVE_SPLIT): one workgroup of sixteen waves per column tile of 32 or
+// M <= 4 (STRIPE): 256-column stripes x S slices of K with S = compute units /
+//   stripes, so that one workgroup runs per compute unit; ten to sixteen waves of
+//   a workgroup own contiguous runs of the slice's rows.
+// M >= 5 (TILE): 64-column tiles x 16, 32 or 64 rows of X per workgroup (as many
+//   rows as still leave a workgroup per compute unit at S = 1), eight waves own
+//   contiguous runs of the slice's K; S again fills the compute units.
+//   Measured crossover at K = 14336, N = 4096: STRIPE 8.7 / 9.1 / 10.8 us at
+//   M = 1 / 2 / 4, TILE 10.6 - 10.7 us for every M <= 16, STRIPE 12.0 us at M = 5.
+//
+// The families below are kept as forced plans (w4a16_gemm_ex) for comparison:
+// WAVE_SPLIT (M <= 4): one workgroup of sixteen waves per column tile of 32 or
 //   64 columns; the sixteen waves are sixteen K slices whose partial results
-//   meet in LDS, so this split costs no memory traffic and no second launch.
-//   64-column tiles when they alone give one workgroup per compute unit, else 32.
-//   A split across workgroups (S > 1: fp32 partials in the workspace and the
-//   second pass, about 3.5 us on this GPU) is added only when the column tiles
-//   cover at most a quarter of the compute units and the slices stay long, which
-//   is where the extra launch costs less than the idle units.
-// 4 < M <= 16 (MFMA_REG): 256-column tiles shared by four waves so that X is read
-//   from L2 once per 256 columns; S fills the GPU with about two workgroups per
-//   compute unit, bounded by the partial-sum traffic (8 S M N bytes written and
-//   read against K N / 2 bytes of weights).
-// M > 16 (MFMA_ROWS): the same tiles with 32 or 64 rows of X per workgroup, so
-//   that each unpacked weight word feeds 2 or 4 MFMAs and W is read once per 32
-//   or 64 rows.
-// How the K slices of different workgroups of a STRIPE plan meet: in the 64-bit fixed-point accumulator (one
+//   meet in LDS.  A split across workgroups is added only when the column tiles
+//   cover at most a quarter of the compute units and the slices stay long.
+// MFMA_REG (M <= 16): 256-column tiles shared by four waves; S fills the GPU with
+//   about two workgroups per compute unit, bounded by the partial-sum traffic
+//   (8 S M N bytes written and read against K N / 2 bytes of weights).
+// MFMA_ROWS: the same tiles with 32 or 64 rows of X per workgroup.
+//
+// How the K slices of different workgroups of a STRIPE or TILE plan meet: in the 64-bit fixed-point accumulator (one
 // returning atomic add per output and slice; measured: the GPU retires about 150 of them per nanosecond)
 // while that is cheaper than a second launch (about 3.3 us, measured), else in the FP32 workspace and the
 // second pass.  Measured crossover: between 0.5 M and 1 M adds.
-bool stripe_meets_in_accumulator(int M, int N, int S)
+bool slices_meet_in_accumulator(int M, int N, int S)
 {
     if (S > 255) return false;
     if (const char *e = getenv("W4A16_STRIPE_FINISH")) {  // tuning aid for sweeps, not part of the contract
@@ -109,7 +114,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
 {
     const int G = K / group;
     if (kernel == W4A16_KERNEL_AUTO)
-        kernel = M <= 16 ? W4A16_KERNEL_STRIPE : W4A16_KERNEL_TILE;
+        kernel = M <= 4 ? W4A16_KERNEL_STRIPE : W4A16_KERNEL_TILE;  // measured crossover (K = 14336, N = 4096): M = 4
     if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG && kernel != W4A16_KERNEL_MFMA_ROWS &&
         kernel != W4A16_KERNEL_STRIPE && kernel != W4A16_KERNEL_TILE)
         return W4A16_ERR_UNSUPPORTED;
@@ -151,7 +156,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->groups_per_split = gps;
         p->workgroups = (int)(tiles * S);
         p->workspace_bytes = S == 1 ? 0
-                             : stripe_meets_in_accumulator(M, N, S) ? (size_t)M * N * sizeof(unsigned long long)
+                             : slices_meet_in_accumulator(M, N, S) ? (size_t)M * N * sizeof(unsigned long long)
                                                                     : (size_t)S * M * N * sizeof(float);
         return W4A16_OK;
     }
@@ -176,7 +181,9 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->split = S;
         p->groups_per_split = gps;
         p->workgroups = (int)(wgs * S);
-        p->workspace_bytes = S > 1 ? (size_t)S * M * N * sizeof(float) : 0;
+        p->workspace_bytes = S == 1 ? 0
+                             : slices_meet_in_accumulator(M, N, S) ? (size_t)M * N * sizeof(unsigned long long)
+                                                                   : (size_t)S * M * N * sizeof(float);
         return W4A16_OK;
     }
     if (kernel == W4A16_KERNEL_WAVE_SPLIT) {
@@ -265,7 +272,7 @@ int ensure_accumulator(int dev, size_t bytes, hipStream_t stream, void **out)
         void *ptr = nullptr;
         hipError_t e = hipMalloc(&ptr, want);
         if (e != hipSuccess) { note_hip_error(e); (void)hipGetLastError(); return W4A16_ERR_WORKSPACE; }
-        e = launch_stripe_clear(static_cast<unsigned long long *>(ptr), want / 8, stream);
+        e = launch_accumulator_clear(static_cast<unsigned long long *>(ptr), want / 8, stream);
         if (e != hipSuccess) { note_hip_error(e); (void)hipFree(ptr); return W4A16_ERR_HIP; }
         d.acc = ptr;
         d.acc_bytes = want;
@@ -293,13 +300,13 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     void *ws = nullptr;
-    const bool in_acc = plan.kernel == W4A16_KERNEL_STRIPE && plan.split > 1 && stripe_meets_in_accumulator(M, N, plan.split);
+    const bool in_acc = (plan.kernel == W4A16_KERNEL_STRIPE || plan.kernel == W4A16_KERNEL_TILE) && plan.split > 1 && slices_meet_in_accumulator(M, N, plan.split);
     if (plan.workspace_bytes) {
         if (user_ws_given) {
             if (user_ws_bytes < plan.workspace_bytes) return W4A16_ERR_WORKSPACE;
             ws = user_ws;
             if (in_acc) {  // a caller's workspace comes uninitialised
-                hipError_t e = launch_stripe_clear(static_cast<unsigned long long *>(ws), (size_t)M * N, st);
+                hipError_t e = launch_accumulator_clear(static_cast<unsigned long long *>(ws), (size_t)M * N, st);
                 if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
             }
         } else if (in_acc) {
@@ -324,7 +331,7 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
 
     hipError_t e = plan.kernel == W4A16_KERNEL_STRIPE
                        ? launch_stripe(a, in_acc ? static_cast<unsigned long long *>(ws) : nullptr, plan.waves_k, st)
-                   : plan.kernel == W4A16_KERNEL_TILE       ? launch_tile(a, plan.tile_m, plan.waves_k, st)
+                   : plan.kernel == W4A16_KERNEL_TILE       ? launch_tile(a, in_acc ? static_cast<unsigned long long *>(ws) : nullptr, plan.tile_m, plan.waves_k, st)
                    : plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st)
                    : plan.kernel == W4A16_KERNEL_MFMA_ROWS  ? launch_mfma_rows(a, plan.tile_m, st)
                                                             : launch_mfma_reg(a, st);

@@ -34,15 +34,17 @@ hipError_t launch_mfma_rows(const GemmArgs &a, int tile_m, hipStream_t stream);
 // of 64-bit words (all zero before and after every launch; split <= 255), or, when acc is null, in
 // a.partials (FP32 [S,M,N]) for the second pass.
 hipError_t launch_stripe(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream);
-hipError_t launch_stripe_clear(unsigned long long *acc, size_t n, hipStream_t stream);
 size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves);  // LDS one workgroup needs
 int stripe_lds_limit();                                                       // most it may use
 int stripe_min_waves(int M);
 int stripe_max_waves(int M);
-// TILE family (meant for M >= 17): 64-column tiles, `rows_x` (16, 32 or 64) rows of X per workgroup,
-// `waves` (4..8) waves per workgroup that split the K slice; split > 1 puts the slices in a.partials.
-hipError_t launch_tile(const GemmArgs &a, int rows_x, int waves, hipStream_t stream);
+// TILE family (the scheduler takes it for M >= 5): 64-column tiles, `rows_x` (16, 32 or 64) rows of X per workgroup,
+// `waves` (4..8) waves per workgroup that split the K slice; with split > 1 the slices meet in `acc`
+// or, when acc is null, in a.partials, as in the STRIPE family.
+hipError_t launch_tile(const GemmArgs &a, unsigned long long *acc, int rows_x, int waves, hipStream_t stream);
 size_t tile_lds_bytes(int rows_x, int waves);
+// Clears n words of a fixed-point accumulator.
+hipError_t launch_accumulator_clear(unsigned long long *acc, size_t n, hipStream_t stream);
 // Second pass (Algorithm 1, Phase 3).
 hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream);
 

@@ -29,7 +29,20 @@ __global__ __launch_bounds__(256) void reduce_kernel(const float *__restrict__ p
     *reinterpret_cast<half4_t *>(Y + i4) = h;
 }
 
+// Clears n words of a fixed-point accumulator (a fill kernel, so that a caller may capture it in a HIP graph).
+__global__ __launch_bounds__(256) void clear_kernel(unsigned long long *p, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
+}
+
 }  // namespace
+
+hipError_t launch_accumulator_clear(unsigned long long *acc, size_t n, hipStream_t stream)
+{
+    hipLaunchKernelGGL(clear_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, acc, n);
+    return hipGetLastError();
+}
 
 hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream)
 {

@@ -45,6 +45,7 @@
 // 4-byte load per block, mostly cache hits): staging them in LDS ahead of the
 // loop instead was measured 1 us slower.
 #include "w4a16_device.h"
+#include "w4a16_finish.h"
 #include "w4a16_internal.h"
 #include <type_traits>
 
@@ -70,29 +71,6 @@ struct Chunk {
     static constexpr int kWaveBytes = 2 * kBufBytes + 16;             // two buffers and the zero entry
 };
 
-// Fixed-point form of a slice sum for the cross-workgroup accumulator: the value
-// in units of 2^-24 (clamped far outside the FP16 range), biased to be positive,
-// in bits 0-55; one arrival in bits 56-63.  Up to 255 slices cannot carry into
-// the count.
-constexpr float kFixScale = 16777216.0f;            // 2^24
-constexpr float kFixClamp = 2097152.0f;             // 2^21
-constexpr unsigned long long kFixBias = 1ull << 46;
-constexpr unsigned long long kFixOne = 1ull << 56;
-
-__device__ __forceinline__ unsigned long long to_fixed(float v)
-{
-    v = fminf(fmaxf(v, -kFixClamp), kFixClamp);
-    const long long fx = (long long)__builtin_rintf(v * kFixScale);  // |v| <= 2^21: the product is exact, |fx| <= 2^45
-    return (unsigned long long)(fx + (long long)kFixBias) + kFixOne;
-}
-
-__device__ __forceinline__ float from_fixed(unsigned long long total)
-{
-    const unsigned long long cnt = total >> 56;
-    const long long fx = (long long)(total & (kFixOne - 1)) - (long long)(cnt * kFixBias);
-    return (float)((double)fx * (1.0 / 16777216.0));
-}
-
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 template <int MROWS>
@@ -103,76 +81,6 @@ struct Mma {
     static constexpr int kMinWaves = wide ? 4 : 1;
     static constexpr int kRedWaves = wide ? 64 / MROWS : 16;         // waves per round of the final sum, at most
 };
-
-// Sum of the waves' results in wave order, `red_waves` waves per round through LDS
-// (red[wave in round][m][column of the stripe]), then the workgroup's finish: Y itself (S = 1), the
-// FP32 partials of the slice, or the fixed-point accumulator.  A thread owns groups of VW neighbouring
-// columns of one row (group o = (row * 256 + column) / VW).
-template <int MROWS>
-struct RowSums {
-    float4_t r[MROWS];  // a lane's four columns, per row of X
-};
-
-template <int MROWS, int VW>
-__device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, unsigned long long *__restrict__ acc, unsigned char *smem,
-                                                  const RowSums<MROWS> tot, int red_waves, int stripe, int slice)
-{
-    typedef float vec_t __attribute__((ext_vector_type(VW)));
-    constexpr int kGroups = MROWS * kStripe / VW;
-    constexpr int kOwn = kGroups / (64 * Mma<MROWS>::kMinWaves);  // groups per thread, at most
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, waves = blockDim.x >> 6;
-    vec_t v[kOwn];
-#pragma unroll
-    for (int k = 0; k < kOwn; ++k) v[k] = vec_t(0.f);
-    const vec_t *red = reinterpret_cast<const vec_t *>(smem);
-    for (int w0 = 0; w0 < waves; w0 += red_waves) {
-        __syncthreads();  // the staged X (first round) or the previous round's sums are no longer needed
-        if (wave >= w0 && wave < w0 + red_waves) {
-            float4_t *mine = reinterpret_cast<float4_t *>(smem) + (size_t)(wave - w0) * MROWS * 64 + lane;
-#pragma unroll
-            for (int i = 0; i < MROWS; ++i) mine[i * 64] = tot.r[i];
-        }
-        __syncthreads();
-        const int nw = waves - w0 < red_waves ? waves - w0 : red_waves;
-#pragma unroll
-        for (int k = 0; k < kOwn; ++k) {
-            if (k * (int)blockDim.x >= kGroups) continue;  // uniform: no thread owns a k-th group
-            const int o = tid + k * (int)blockDim.x;
-            const int oc = o < kGroups ? o : 0;  // threads past the last group read group 0 and store nothing
-            // four reads in flight at a time (past the last wave the last one is read again and not added)
-            for (int w = 0; w < nw; w += 4) {
-                vec_t t0 = red[(size_t)w * kGroups + oc];
-                vec_t t1 = red[(size_t)(w + 1 < nw ? w + 1 : nw - 1) * kGroups + oc];
-                vec_t t2 = red[(size_t)(w + 2 < nw ? w + 2 : nw - 1) * kGroups + oc];
-                vec_t t3 = red[(size_t)(w + 3 < nw ? w + 3 : nw - 1) * kGroups + oc];
-                v[k] += t0;
-                if (w + 1 < nw) v[k] += t1;
-                if (w + 2 < nw) v[k] += t2;
-                if (w + 3 < nw) v[k] += t3;
-            }
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < kOwn; ++k) {
-        const int o = tid + k * (int)blockDim.x;
-        const int m = o / (kStripe / VW), col = stripe * kStripe + VW * (o % (kStripe / VW));
-        if (o >= kGroups || m >= a.M || col >= a.N) continue;
-        const size_t out = (size_t)m * a.N + col;
-        if constexpr (VW == 4) {
-            if (a.split == 1)
-                *reinterpret_cast<uint2_t *>(a.Y + out) = (uint2_t){pack_half2(v[k][0], v[k][1]), pack_half2(v[k][2], v[k][3])};
-            else
-                *reinterpret_cast<float4_t *>(a.partials + (size_t)slice * a.M * a.N + out) = v[k];
-        } else {
-            const unsigned long long add = to_fixed(v[k][0]);
-            const unsigned long long total = __hip_atomic_fetch_add(acc + out, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
-            if ((total >> 56) == (unsigned long long)a.split) {
-                a.Y[out] = (uint16_t)(pack_half2(from_fixed(total), 0.f) & 0xFFFFu);
-                __hip_atomic_store(acc + out, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-    }
-}
 
 template <int MROWS>
 __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const GemmArgs a, unsigned long long *__restrict__ acc, const int red_waves)
@@ -371,19 +279,14 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
     // Phase 3 inside the workgroup, then across workgroups.  The atomic finish wants consecutive lanes on
     // consecutive outputs (one 8-byte atomic per lane: four cache lines per wave-wide instruction); the
     // other finishes move four neighbouring outputs per lane.
-    RowSums<MROWS> sums;
+    const auto write_mine = [&](float4_t *mine) {  // [row][column / 4] of this wave's 256 columns
 #pragma unroll
-    for (int i = 0; i < MROWS; ++i) sums.r[i] = (float4_t){tot[0][i], tot[1][i], tot[2][i], tot[3][i]};
+        for (int i = 0; i < MROWS; ++i) mine[i * 64 + lane] = (float4_t){tot[0][i], tot[1][i], tot[2][i], tot[3][i]};
+    };
     if (a.split > 1 && !a.partials)
-        reduce_and_finish<MROWS, 1>(a, acc, smem, sums, red_waves, stripe, slice);
+        reduce_and_finish<MROWS, kStripe, 1, Mma<MROWS>::kMinWaves>(a, acc, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
     else
-        reduce_and_finish<MROWS, 4>(a, acc, smem, sums, red_waves, stripe, slice);
-}
-
-__global__ __launch_bounds__(256) void clear_kernel(unsigned long long *p, size_t n)
-{
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0ull;
+        reduce_and_finish<MROWS, kStripe, 4, Mma<MROWS>::kMinWaves>(a, acc, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
 }
 
 int mrows_of(int M) { return M == 1 ? 1 : (M == 2 ? 2 : (M <= 4 ? 4 : (M <= 8 ? 8 : 16))); }
@@ -435,12 +338,6 @@ size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves)
     size_t red = one * waves;
     if (red > 64 * 1024) red = 64 * 1024 < one ? one : 64 * 1024 / one * one;
     return stage > red ? stage : red;
-}
-
-hipError_t launch_stripe_clear(unsigned long long *acc, size_t n, hipStream_t stream)
-{
-    hipLaunchKernelGGL(clear_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, acc, n);
-    return hipGetLastError();
 }
 
 // `acc` != null: the slices meet in the fixed-point accumulator; else a.partials (FP32 [S, M, N]) takes them

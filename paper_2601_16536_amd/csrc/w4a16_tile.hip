@@ -1,8 +1,9 @@
-// W4A16 multiply for M >= 17: one workgroup per (64-column tile, block of 16 RT
+// W4A16 multiply for M >= 5: one workgroup per (64-column tile, block of 16 RT
 // rows of X, K slice), RT = 1, 2 or 4.  The waves of a workgroup own contiguous
 // runs of the slice's K (Algorithm 1, Phase 2 with the slices held by waves) and
 // their results meet in LDS; with S = 1 the workgroup casts and stores Y itself,
-// with S > 1 the slices go to the FP32 workspace and the second pass (Phase 3).
+// with S > 1 the slices meet in the fixed-point accumulator or go to the FP32
+// workspace and the second pass (Phase 3), as in the STRIPE family.
 //
 // Operands of the 16x16x32 MFMA in its plain form: a lane's 32-bit word (eight k
 // of one column) is its B-operand slice, lane (g, j) holding packed row 4 b + g
@@ -25,6 +26,7 @@
 // numbered so that they sit on the same XCD (workgroup b runs on XCD b mod 8) and
 // start together: the second reader finds the weights in that XCD's L2.
 #include "w4a16_device.h"
+#include "w4a16_finish.h"
 #include "w4a16_internal.h"
 
 namespace w4a16 {
@@ -48,7 +50,7 @@ struct Shape {
 };
 
 template <int RT>
-__global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int row_blocks, const int red_waves)
+__global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, unsigned long long *__restrict__ acc, const int row_blocks, const int red_waves)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     typedef Shape<RT> Sh;
@@ -232,59 +234,22 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int r
         }
     }
 
-    // Sum over the waves in wave order, red_waves waves per round through LDS: red[wave in round][row][column].
-    // A thread owns groups of four neighbouring columns of one row.
-    constexpr int kGroups = Sh::kRowsX * kTileCols / 4;
-    constexpr int kOwn = (kGroups + 255) / 256;  // at least four waves
-    float4_t v[kOwn];
+    // Phase 3 inside the workgroup, then across workgroups (see w4a16_finish.h).
+    const auto write_mine = [&](float4_t *mine) {  // [row][column / 4] of the 64-column tile
 #pragma unroll
-    for (int k = 0; k < kOwn; ++k) v[k] = (float4_t){0.f, 0.f, 0.f, 0.f};
-    const float4_t *red = reinterpret_cast<const float4_t *>(smem);
-    for (int w0 = 0; w0 < waves; w0 += red_waves) {
-        __syncthreads();  // the staged X (first round) or the previous round's sums are no longer needed
-        if (wave >= w0 && wave < w0 + red_waves) {
-            float4_t *mine = reinterpret_cast<float4_t *>(smem) + (size_t)(wave - w0) * kGroups;
+        for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] =
-                        (float4_t){tot[rt][0][i], tot[rt][1][i], tot[rt][2][i], tot[rt][3][i]};
-        }
-        __syncthreads();
-        const int nw = waves - w0 < red_waves ? waves - w0 : red_waves;
-#pragma unroll
-        for (int k = 0; k < kOwn; ++k) {
-            if (k * (int)blockDim.x >= kGroups) continue;  // uniform: no thread owns a k-th group
-            const int o = tid + k * (int)blockDim.x;
-            const int oc = o < kGroups ? o : 0;  // threads past the last group read group 0 and store nothing
-            for (int w = 0; w < nw; w += 4) {  // four reads in flight at a time
-                const float4_t t0 = red[(size_t)w * kGroups + oc];
-                const float4_t t1 = red[(size_t)(w + 1 < nw ? w + 1 : nw - 1) * kGroups + oc];
-                const float4_t t2 = red[(size_t)(w + 2 < nw ? w + 2 : nw - 1) * kGroups + oc];
-                const float4_t t3 = red[(size_t)(w + 3 < nw ? w + 3 : nw - 1) * kGroups + oc];
-                v[k] += t0;
-                if (w + 1 < nw) v[k] += t1;
-                if (w + 2 < nw) v[k] += t2;
-                if (w + 3 < nw) v[k] += t3;
-            }
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < kOwn; ++k) {
-        const int o = tid + k * (int)blockDim.x;
-        const int m = m0 + o / (kTileCols / 4), col = tile * kTileCols + 4 * (o % (kTileCols / 4));
-        if (o >= kGroups || m >= a.M || col >= a.N) continue;
-        const size_t out = (size_t)m * a.N + col;
-        if (a.split == 1)
-            *reinterpret_cast<uint2_t *>(a.Y + out) = (uint2_t){pack_half2(v[k][0], v[k][1]), pack_half2(v[k][2], v[k][3])};
-        else
-            *reinterpret_cast<float4_t *>(a.partials + (size_t)slice * a.M * a.N + out) = v[k];
-    }
+            for (int i = 0; i < 4; ++i)
+                mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = (float4_t){tot[rt][0][i], tot[rt][1][i], tot[rt][2][i], tot[rt][3][i]};
+    };
+    if (a.split > 1 && !a.partials)
+        reduce_and_finish<Sh::kRowsX, kTileCols, 1, 4>(a, acc, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+    else
+        reduce_and_finish<Sh::kRowsX, kTileCols, 4, 4>(a, acc, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
 }
 
 template <int RT>
-hipError_t launch_rt(const GemmArgs &a, int waves, hipStream_t stream)
+hipError_t launch_rt(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream)
 {
     typedef Shape<RT> Sh;
     const size_t lds = tile_lds_bytes(Sh::kRowsX, waves);
@@ -304,7 +269,7 @@ hipError_t launch_rt(const GemmArgs &a, int waves, hipStream_t stream)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((tile_kernel<RT>), dim3((unsigned)grid), dim3(waves * 64), lds, stream, a, row_blocks, red_waves);
+    hipLaunchKernelGGL((tile_kernel<RT>), dim3((unsigned)grid), dim3(waves * 64), lds, stream, a, acc, row_blocks, red_waves);
     return hipGetLastError();
 }
 
@@ -320,13 +285,16 @@ size_t tile_lds_bytes(int rows_x, int waves)
     return stage > red ? stage : red;
 }
 
-hipError_t launch_tile(const GemmArgs &a, int rows_x, int waves, hipStream_t stream)
+hipError_t launch_tile(const GemmArgs &a, unsigned long long *acc, int rows_x, int waves, hipStream_t stream)
 {
     if (waves < 4 || waves > 8 || a.group % (8 * kBlockRows) != 0) return hipErrorInvalidValue;
-    if (a.split > 1 && !a.partials) return hipErrorInvalidValue;
-    if (rows_x == 16) return launch_rt<1>(a, waves, stream);
-    if (rows_x == 32) return launch_rt<2>(a, waves, stream);
-    if (rows_x == 64) return launch_rt<4>(a, waves, stream);
+    if (a.split > 1 && !acc && !a.partials) return hipErrorInvalidValue;
+    if (a.split > 1 && acc && a.split > 255) return hipErrorInvalidValue;
+    GemmArgs b = a;
+    if (acc || a.split == 1) b.partials = nullptr;  // the kernel reads the finish mode off this pointer
+    if (rows_x == 16) return launch_rt<1>(b, acc, waves, stream);
+    if (rows_x == 32) return launch_rt<2>(b, acc, waves, stream);
+    if (rows_x == 64) return launch_rt<4>(b, acc, waves, stream);
     return hipErrorInvalidValue;
 }
 
