@@ -170,7 +170,15 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         // the FP32 partials and the second pass).
         int rows_x = 64;
         while (rows_x > 16 && (rows_x / 2 >= M || tiles * ((M + rows_x - 1) / rows_x) < cus)) rows_x /= 2;
+        if (const char *e = getenv("W4A16_TILE_ROWS")) {  // tuning aid for sweeps, not part of the contract
+            const int r = atoi(e);
+            if (r == 16 || r == 32 || r == 64) rows_x = r;
+        }
         p->tile_m = rows_x;
+        if (const char *e = getenv("W4A16_TILE_WAVES")) {  // tuning aid for sweeps, not part of the contract
+            const int w = atoi(e);
+            if (w >= 4 && w <= 8) { p->waves_k = w; p->threads = 64 * w; }
+        }
         const long long wgs = tiles * ((M + rows_x - 1) / rows_x);
         if (S == 0) S = (int)((cus + wgs / 2) / wgs);
         if (S < 1) S = 1;

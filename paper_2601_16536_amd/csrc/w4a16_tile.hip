@@ -28,6 +28,7 @@
 #include "w4a16_device.h"
 #include "w4a16_finish.h"
 #include "w4a16_internal.h"
+#include <type_traits>
 
 namespace w4a16 {
 namespace {
@@ -248,11 +249,226 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, unsigned lo
         reduce_and_finish<Sh::kRowsX, kTileCols, 4, 4>(a, acc, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
 }
 
+// ---- group = 128: the waves' runs are whole quantisation groups ----
+//
+// With four blocks to the group a wave's loop can be laid out around the group: the scales and zero
+// points are read once per group (not with every block), the step of Eq. 2 sits at a fixed place (no
+// test per block), each group's MFMA sums start from a zero operand (no clearing), and the weights of
+// two groups (eight blocks, 8 KB per wave) are in flight, which is what the memory latency of about
+// 1.3 us asks for at eight waves per compute unit.  Every buffer descriptor ends where the wave's run
+// ends, so loads past the run are cut off by the hardware's range check (zeros, no traffic) and need
+// no test either.
+template <int RT>
+struct GroupShape {
+    static constexpr int kRowsX = 16 * RT;
+    static constexpr int kChunkBlocks = RT == 4 ? 1 : 4;         // blocks per staged chunk of X
+    static constexpr int kChunks = 4 / kChunkBlocks;             // chunks per group
+    static constexpr int kRingGroups = RT == 4 ? 1 : 2;          // groups of weights in flight per wave (registers)
+    static constexpr int kRowStride = kRowsX + 4;                // LDS entries per packed row (padded)
+    static constexpr int kPerLane = kChunkBlocks * kBlockRows * kRowsX / 64;
+    static constexpr int kBufBytes = kChunkBlocks * kBlockRows * kRowStride * 16;
+    static constexpr int kWaveBytes = 2 * kBufBytes;
+    static constexpr int kOutBytes = kRowsX * kTileCols * 4;
+};
+
+template <int RT>
+__global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, unsigned long long *__restrict__ acc, const int row_blocks, const int red_waves)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    typedef GroupShape<RT> Sh;
+    constexpr int kBpg = 4;  // blocks per group
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int waves = blockDim.x >> 6;
+    const int g4 = lane >> 4, j = lane & 15;
+
+    const int ntiles = (a.N + kTileCols - 1) / kTileCols;
+    const int units = ntiles * a.split;
+    const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+    const int rb = local % row_blocks, unit = (local / row_blocks) * kXcds + xcd;
+    if (unit >= units) return;  // the grid is rounded up to whole XCD rounds
+    const int tile = unit % ntiles, slice = unit / ntiles;
+    const int m0 = rb * Sh::kRowsX;
+    const int col0 = tile * kTileCols + 4 * j;
+    const bool ok = col0 < a.N;
+
+    // the slice's groups, and this wave's run of them
+    const int gbeg = slice * a.groups_per_split;
+    int gend = gbeg + a.groups_per_split;
+    if (gend > a.K / a.group) gend = a.K / a.group;
+    const int groups = gend - gbeg;
+    const int g0 = gbeg + (int)((long long)groups * wave / waves);
+    const int g1 = gbeg + (int)((long long)groups * (wave + 1) / waves);
+    const int ng = g1 - g0;
+
+    const uint32_t row_w = (uint32_t)a.N * 4u, row_s = (uint32_t)a.N * 2u, row_z = (uint32_t)(a.N >> 3) * 4u;
+    const uint32_t step_w = kBlockRows * row_w;  // one block further
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t *>(a.Wp) + (size_t)g0 * 16 * a.N, 0, (uint32_t)ng * 16u * row_w, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(a.scales) + (size_t)g0 * a.N, 0, (uint32_t)ng * row_s, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t *>(a.Zp) + (size_t)g0 * (a.N >> 3), 0, (uint32_t)ng * row_z, kRawBuffer);
+    // running per-lane offsets of the next block / group to load; the range check is on these
+    uint32_t vw = ok ? (uint32_t)(g4 * a.N + col0) * 4u : kOutOfRange;
+    uint32_t vs = ok ? (uint32_t)col0 * 2u : kOutOfRange;
+    uint32_t vz = ok ? (uint32_t)(col0 >> 3) * 4u : kOutOfRange;
+
+    constexpr int kRG = Sh::kRingGroups;
+    uint4_t wq[kRG * kBpg];  // the weights in flight
+    auto load_w = [&](uint4_t &d) {
+        d = __builtin_amdgcn_raw_buffer_load_b128(rw, vw, 0, 2);  // read once from DRAM: nontemporal
+        vw += step_w;
+    };
+
+    // ---- X: this wave's LDS (two chunk buffers), chunk loader and chunk writer ----
+    // Entry e = lane + 64 q of a chunk: packed row e & 3 of block (e >> 2) / rows of row (e >> 2) % rows of X,
+    // so four neighbouring lanes fetch 64 contiguous bytes.  For every q the row is (lane >> 2) + 16 (q % RT)
+    // and the block is q / RT: per lane one global offset per q % RT and one LDS slot, the rest are constants.
+    unsigned char *wl = smem + (size_t)wave * Sh::kWaveBytes;
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(a.X), 0, (uint32_t)((size_t)a.M * a.K * 2), kRawBuffer);
+    uint32_t xg[RT];
+#pragma unroll
+    for (int s = 0; s < RT; ++s) {
+        const uint32_t m = (uint32_t)m0 + (uint32_t)(lane >> 2) + 16u * s;
+        xg[s] = m < (uint32_t)a.M ? (m * (uint32_t)a.K + ((uint32_t)g0 * 16u + (uint32_t)(lane & 3)) * 8u) * 2u : kOutOfRange;
+    }
+    const uint32_t xl0 = (uint32_t)(((lane & 3) * Sh::kRowStride + (lane >> 2)) * 16);
+    uint4_t xd[Sh::kPerLane];
+    auto x_load = [&](uint32_t chunk) {  // chunk of the wave's run
+        const uint32_t so = chunk * (Sh::kChunkBlocks * kBlockRows * 16u);
+#pragma unroll
+        for (int q = 0; q < Sh::kPerLane; ++q)
+            xd[q] = __builtin_amdgcn_raw_buffer_load_b128(rx, xg[q % RT], so + (q / RT) * (kBlockRows * 16u), 0);
+    };
+    auto x_store = [&](int par) {
+#pragma unroll
+        for (int q = 0; q < Sh::kPerLane; ++q)
+            *reinterpret_cast<uint4_t *>(wl + par * Sh::kBufBytes + xl0 + ((q / RT) * kBlockRows * Sh::kRowStride + 16 * (q % RT)) * 16) = permute_x(xd[q]);
+    };
+
+    float4_t tot[RT][4];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) tot[rt][c] = (float4_t){0.f, 0.f, 0.f, 0.f};
+
+    if (ng > 0) {
+        // X of the first chunk goes ahead of the weights: loads return in order, and X (mostly cache hits)
+        // must not queue behind the first weight blocks.
+        x_load(0);
+#pragma unroll
+        for (int h = 0; h < kRG; ++h)
+#pragma unroll
+            for (int p = 0; p < kBpg; ++p) load_w(wq[h * kBpg + p]);
+        x_store(0);
+
+        const uint32_t xa0 = (uint32_t)(wave * Sh::kWaveBytes + (g4 * Sh::kRowStride + j) * 16);  // A entry of block 0, row tile 0
+        const uint32_t zsh = (uint32_t)(col0 & 4) * 4u;  // this lane's four nibbles in its zero-point word
+        const Masks masks = make_masks();
+        // sum_k x_k over a group comes from the MFMA too: X against ones (16 where the staged x was divided by 16)
+        const half8_t ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f, (_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f};
+        const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
+
+        // One group: its four blocks from ring half H, chunk buffers by parity of the chunk number.  Only this
+        // wave touches its LDS and the LDS operations of one wave complete in order; the fences only keep the
+        // compiler from moving them across the staging.
+        auto do_group = [&](auto half, const uint32_t gi) {
+            constexpr int H = decltype(half)::value;  // parity of the group in the run: its chunk buffers
+            constexpr int R = H % kRG;                 // its place in the ring
+            float4_t part[RT][4], xsum[RT];
+            // The group's scales and zero points, wanted when its four blocks are done.  Loads return in order:
+            // these come in behind the weights of the groups in flight, which are wanted earlier anyway.
+            const uint2_t sc = __builtin_amdgcn_raw_buffer_load_b64(rs, vs, 0, 0);
+            const uint32_t zw = __builtin_amdgcn_raw_buffer_load_b32(rz, vz, 0, 0);
+            vs += row_s;
+            vz += row_z;
+#pragma unroll
+            for (int p = 0; p < kBpg; ++p) {
+                constexpr int CB = Sh::kChunkBlocks;
+                const int c = p / CB, lb = p % CB;
+                const int par = (H * Sh::kChunks + c) & 1;
+                const bool more = c + 1 < Sh::kChunks || gi + 1 < (uint32_t)ng;  // a chunk follows this one
+                if (lb == 0 && more) x_load(gi * Sh::kChunks + c + 1);
+                const unsigned char *xb = smem + xa0 + par * Sh::kBufBytes + lb * (kBlockRows * Sh::kRowStride * 16);
+                half8_t bop[4];
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) bop[cc] = unpack8(wq[R * kBpg + p][cc], masks);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    H8 x;
+                    x.u = *reinterpret_cast<const uint4_t *>(xb + rt * 256);
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc)
+                        part[rt][cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, bop[cc], p == 0 ? zero4 : part[rt][cc], 0, 0, 0);
+                    xsum[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, ones, p == 0 ? zero4 : xsum[rt], 0, 0, 0);
+                }
+                load_w(wq[R * kBpg + p]);  // the same block kRG groups on
+                if (lb == CB - 1 && more) {
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    x_store(par ^ 1);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                }
+            }
+            // the group is done: scale and zero point (Eq. 2)
+            H2 s01, s23;
+            s01.u = sc[0];
+            s23.u = sc[1];
+            const float s[4] = {(float)s01.h[0], (float)s01.h[1], (float)s23.h[0], (float)s23.h[1]};
+            const uint32_t z = zw >> zsh;
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                const float sp = s[cc] * 16777216.0f;                      // 2^24 s
+                const float sz = -s[cc] * (float)((z >> (4 * cc)) & 15u);  // -s z
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        tot[rt][cc][i] = __builtin_fmaf(sp, part[rt][cc][i], __builtin_fmaf(sz, xsum[rt][i], tot[rt][cc][i]));
+            }
+        };
+
+        for (uint32_t gi = 0; gi < (uint32_t)ng; gi += 2) {
+            do_group(std::integral_constant<int, 0>{}, gi);
+            if (gi + 1 < (uint32_t)ng) do_group(std::integral_constant<int, 1>{}, gi + 1);
+        }
+    }
+
+    // Phase 3 inside the workgroup, then across workgroups (see w4a16_finish.h).
+    const auto write_mine = [&](float4_t *mine) {  // [row][column / 4] of the 64-column tile
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = (float4_t){tot[rt][0][i], tot[rt][1][i], tot[rt][2][i], tot[rt][3][i]};
+    };
+    if (a.split > 1 && !a.partials)
+        reduce_and_finish<Sh::kRowsX, kTileCols, 1, 4>(a, acc, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+    else
+        reduce_and_finish<Sh::kRowsX, kTileCols, 4, 4>(a, acc, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+}
+
+size_t lds_bytes(int rows_x, int waves, bool by_group)
+{
+    const size_t wave_bytes = by_group ? (rows_x == 16 ? GroupShape<1>::kWaveBytes : rows_x == 32 ? GroupShape<2>::kWaveBytes : GroupShape<4>::kWaveBytes)
+                                       : (rows_x == 16 ? Shape<1>::kWaveBytes : rows_x == 32 ? Shape<2>::kWaveBytes : Shape<4>::kWaveBytes);
+    const size_t stage = (size_t)waves * wave_bytes;
+    // the final sums reuse the space, a whole number of waves' tiles per round
+    const size_t one = (size_t)rows_x * kTileCols * 4;
+    size_t red = one * waves;
+    if (red > 64 * 1024) red = 64 * 1024 / one * one;
+    return stage > red ? stage : red;
+}
+
 template <int RT>
 hipError_t launch_rt(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream)
 {
     typedef Shape<RT> Sh;
-    const size_t lds = tile_lds_bytes(Sh::kRowsX, waves);
+    const bool by_group = a.group == 128;
+    const size_t lds = lds_bytes(Sh::kRowsX, waves, by_group);
     int red_waves = (int)(lds / Sh::kOutBytes);
     if (red_waves < 1) return hipErrorInvalidValue;
     if (red_waves > waves) red_waves = waves;
@@ -264,26 +480,21 @@ hipError_t launch_rt(const GemmArgs &a, unsigned long long *acc, int waves, hipS
     const long long units = (long long)ntiles * a.split;
     const long long grid = (units + kXcds - 1) / kXcds * kXcds * row_blocks;
     if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const void *fn = by_group ? reinterpret_cast<const void *>(&tile_group_kernel<RT>) : reinterpret_cast<const void *>(&tile_kernel<RT>);
     if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_kernel<RT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((tile_kernel<RT>), dim3((unsigned)grid), dim3(waves * 64), lds, stream, a, acc, row_blocks, red_waves);
+    if (by_group)
+        hipLaunchKernelGGL((tile_group_kernel<RT>), dim3((unsigned)grid), dim3(waves * 64), lds, stream, a, acc, row_blocks, red_waves);
+    else
+        hipLaunchKernelGGL((tile_kernel<RT>), dim3((unsigned)grid), dim3(waves * 64), lds, stream, a, acc, row_blocks, red_waves);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// The waves' chunk buffers; the final sums reuse the space, a whole number of waves' tiles per round.
-size_t tile_lds_bytes(int rows_x, int waves)
-{
-    const size_t stage = (size_t)waves * (rows_x == 16 ? Shape<1>::kWaveBytes : rows_x == 32 ? Shape<2>::kWaveBytes : Shape<4>::kWaveBytes);
-    const size_t one = (size_t)rows_x * kTileCols * 4;
-    size_t red = one * waves;
-    if (red > 64 * 1024) red = 64 * 1024 / one * one;
-    return stage > red ? stage : red;
-}
+size_t tile_lds_bytes(int rows_x, int waves) { return lds_bytes(rows_x, waves, true); }
 
 hipError_t launch_tile(const GemmArgs &a, unsigned long long *acc, int rows_x, int waves, hipStream_t stream)
 {
