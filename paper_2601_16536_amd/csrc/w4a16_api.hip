@@ -19,7 +19,7 @@ struct DeviceState {
     int cus = 0;             // compute units (0 = not read yet)
     void *ws = nullptr;      // library-owned workspace (fp32 partials of the two-pass plans)
     size_t ws_bytes = 0;
-    void *acc = nullptr;     // library-owned fixed-point accumulator of the STRIPE family: all zero between calls
+    void *acc = nullptr;     // library-owned fixed-point accumulator of the STRIPE and TILE families: all zero between calls
     size_t acc_bytes = 0;
 };
 
@@ -99,7 +99,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // How the K slices of different workgroups of a STRIPE or TILE plan meet: in the 64-bit fixed-point accumulator (one
 // returning atomic add per output and slice; measured: the GPU retires about 150 of them per nanosecond)
 // while that is cheaper than a second launch (about 3.3 us, measured), else in the FP32 workspace and the
-// second pass.  Measured crossover: between 0.5 M and 1 M adds.
+// second pass.  Measured crossover: between 0.5 M and 1 M adds.  The other families always take the second pass.
 bool slices_meet_in_accumulator(int M, int N, int S)
 {
     if (S > 255) return false;
@@ -108,6 +108,23 @@ bool slices_meet_in_accumulator(int M, int N, int S)
         if (e[0] == 'w') return false;
     }
     return (long long)S * M * N <= 640 * 1024;
+}
+
+int finish_of(int kernel, int M, int N, int S)
+{
+    if (S == 1) return kFinishDirect;
+    if (kernel != W4A16_KERNEL_STRIPE && kernel != W4A16_KERNEL_TILE) return kFinishSecondPass;
+    return slices_meet_in_accumulator(M, N, S) ? kFinishAccumulator : kFinishSecondPass;
+}
+
+// Workspace of a plan: nothing, the accumulator [M, N], or the FP32 partials [S, M, N].
+size_t workspace_of(int kernel, int M, int N, int S)
+{
+    switch (finish_of(kernel, M, N, S)) {
+    case kFinishDirect: return 0;
+    case kFinishAccumulator: return (size_t)M * N * sizeof(unsigned long long);
+    default: return (size_t)S * M * N * sizeof(float);
+    }
 }
 
 int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4a16_plan *p)
@@ -155,9 +172,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->split = S;
         p->groups_per_split = gps;
         p->workgroups = (int)(tiles * S);
-        p->workspace_bytes = S == 1 ? 0
-                             : slices_meet_in_accumulator(M, N, S) ? (size_t)M * N * sizeof(unsigned long long)
-                                                                    : (size_t)S * M * N * sizeof(float);
+        p->workspace_bytes = workspace_of(kernel, M, N, S);
         return W4A16_OK;
     }
     if (kernel == W4A16_KERNEL_TILE) {
@@ -189,9 +204,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->split = S;
         p->groups_per_split = gps;
         p->workgroups = (int)(wgs * S);
-        p->workspace_bytes = S == 1 ? 0
-                             : slices_meet_in_accumulator(M, N, S) ? (size_t)M * N * sizeof(unsigned long long)
-                                                                   : (size_t)S * M * N * sizeof(float);
+        p->workspace_bytes = workspace_of(kernel, M, N, S);
         return W4A16_OK;
     }
     if (kernel == W4A16_KERNEL_WAVE_SPLIT) {
@@ -236,7 +249,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
     p->split = S;
     p->groups_per_split = gps;
     p->workgroups = (int)(tiles * S);
-    p->workspace_bytes = S > 1 ? (size_t)S * M * N * sizeof(float) : 0;
+    p->workspace_bytes = workspace_of(kernel, M, N, S);
     return W4A16_OK;
 }
 
@@ -263,7 +276,7 @@ int ensure_workspace(int dev, size_t bytes, void **out)
     return W4A16_OK;
 }
 
-// The STRIPE family's accumulator: grown on demand, cleared once when allocated (on `stream`,
+// The accumulator of the STRIPE and TILE families: grown on demand, cleared once when allocated (on `stream`,
 // ahead of the launch that first uses it); every launch leaves it all zero again.
 int ensure_accumulator(int dev, size_t bytes, hipStream_t stream, void **out)
 {
@@ -307,23 +320,28 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
     if (rc) return rc;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    void *ws = nullptr;
-    const bool in_acc = (plan.kernel == W4A16_KERNEL_STRIPE || plan.kernel == W4A16_KERNEL_TILE) && plan.split > 1 && slices_meet_in_accumulator(M, N, plan.split);
-    if (plan.workspace_bytes) {
-        if (user_ws_given) {
-            if (user_ws_bytes < plan.workspace_bytes) return W4A16_ERR_WORKSPACE;
-            ws = user_ws;
-            if (in_acc) {  // a caller's workspace comes uninitialised
-                hipError_t e = launch_accumulator_clear(static_cast<unsigned long long *>(ws), (size_t)M * N, st);
-                if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
-            }
-        } else if (in_acc) {
-            rc = ensure_accumulator(dev, plan.workspace_bytes, st, &ws);
-            if (rc) return rc;
+    const int finish = finish_of(plan.kernel, M, N, plan.split);
+    unsigned long long *sync = nullptr;  // the accumulator: zero before the launch, left zero by it
+    float *partials = nullptr;
+    if (user_ws_given && user_ws_bytes < plan.workspace_bytes) return W4A16_ERR_WORKSPACE;
+    if (finish == kFinishAccumulator) {
+        if (user_ws_given) {  // a caller's workspace comes uninitialised
+            sync = static_cast<unsigned long long *>(user_ws);
+            hipError_t e = launch_accumulator_clear(sync, (size_t)M * N, st);
+            if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
         } else {
-            rc = ensure_workspace(dev, plan.workspace_bytes, &ws);
+            void *ptr = nullptr;
+            rc = ensure_accumulator(dev, plan.workspace_bytes, st, &ptr);
+            if (rc) return rc;
+            sync = static_cast<unsigned long long *>(ptr);
+        }
+    } else if (finish == kFinishSecondPass) {
+        void *ptr = user_ws;
+        if (!user_ws_given) {
+            rc = ensure_workspace(dev, plan.workspace_bytes, &ptr);
             if (rc) return rc;
         }
+        partials = static_cast<float *>(ptr);
     }
 
     GemmArgs a;
@@ -332,19 +350,18 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
     a.scales = static_cast<const uint16_t *>(scales);
     a.Zp = zeros;
     a.Y = static_cast<uint16_t *>(Y);
-    a.partials = static_cast<float *>(ws);
+    a.partials = partials;
     a.group = group; a.M = M; a.N = N; a.K = K;
     a.split = plan.split;
     a.groups_per_split = plan.groups_per_split;
 
-    hipError_t e = plan.kernel == W4A16_KERNEL_STRIPE
-                       ? launch_stripe(a, in_acc ? static_cast<unsigned long long *>(ws) : nullptr, plan.waves_k, st)
-                   : plan.kernel == W4A16_KERNEL_TILE       ? launch_tile(a, in_acc ? static_cast<unsigned long long *>(ws) : nullptr, plan.tile_m, plan.waves_k, st)
+    hipError_t e = plan.kernel == W4A16_KERNEL_STRIPE       ? launch_stripe(a, finish, sync, plan.waves_k, st)
+                   : plan.kernel == W4A16_KERNEL_TILE       ? launch_tile(a, finish, sync, plan.tile_m, plan.waves_k, st)
                    : plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st)
                    : plan.kernel == W4A16_KERNEL_MFMA_ROWS  ? launch_mfma_rows(a, plan.tile_m, st)
                                                             : launch_mfma_reg(a, st);
     if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
-    if (plan.split > 1 && !in_acc) {
+    if (finish == kFinishSecondPass) {
         e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);
         if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
     }

@@ -58,10 +58,11 @@ __device__ __forceinline__ uint4_t permute_x(uint4_t d)
 {
     const half2_t sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
     H2 p0, p1, p2, p3;
-    p0.u = (d[0] & 0xFFFFu) | (d[2] << 16);      // x0, x4
-    p1.u = (d[0] >> 16) | (d[2] & 0xFFFF0000u);  // x1, x5
-    p2.u = (d[1] & 0xFFFFu) | (d[3] << 16);      // x2, x6
-    p3.u = (d[1] >> 16) | (d[3] & 0xFFFF0000u);  // x3, x7
+    // byte selectors of v_perm_b32: 0-3 pick from the second operand, 4-7 from the first
+    p0.u = __builtin_amdgcn_perm(d[2], d[0], 0x05040100u);  // x0, x4
+    p1.u = __builtin_amdgcn_perm(d[2], d[0], 0x07060302u);  // x1, x5
+    p2.u = __builtin_amdgcn_perm(d[3], d[1], 0x05040100u);  // x2, x6
+    p3.u = __builtin_amdgcn_perm(d[3], d[1], 0x07060302u);  // x3, x7
     p1.h = p1.h * sixteenth;
     p3.h = p3.h * sixteenth;
     return (uint4_t){p0.u, p1.u, p2.u, p3.u};

@@ -32,11 +32,12 @@ __device__ __forceinline__ float from_fixed(unsigned long long total)
 
 // Sum of the waves' result tiles (ROWS x COLS each) in wave order, `red_waves` waves per round through
 // LDS (red[wave in round][row][column]; `write_mine` puts the calling wave's tile there as float4
-// groups), then the workgroup's finish: Y itself (S = 1), the FP32 partials of the slice, or the
-// fixed-point accumulator.  A thread owns groups of VW neighbouring columns of one row.  The atomic
-// finish wants VW = 1: consecutive lanes on consecutive outputs, four cache lines per wave-wide atomic.
+// groups), then the workgroup's finish.  A thread owns groups of VW neighbouring columns of one row;
+// the atomic finish wants VW = 1 (consecutive lanes on consecutive outputs, four cache lines per
+// wave-wide atomic), the others VW = 4.  `sync` is the accumulator [M, N] (64-bit words, all zero
+// before the launch and left zero by it).
 template <int ROWS, int COLS, int VW, int MIN_WAVES, typename WriteMine>
-__device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, unsigned long long *__restrict__ acc, unsigned char *smem,
+__device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int finish, unsigned long long *__restrict__ sync, unsigned char *smem,
                                                   const WriteMine &write_mine, int red_waves, int row0, int col0, int slice)
 {
     typedef float vec_t __attribute__((ext_vector_type(VW)));
@@ -78,16 +79,16 @@ __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, unsigned lo
         if (o >= kGroups || m >= a.M || col >= a.N) continue;
         const size_t out = (size_t)m * a.N + col;
         if constexpr (VW == 4) {
-            if (a.split == 1)
+            if (finish == kFinishDirect)
                 *reinterpret_cast<uint2_t *>(a.Y + out) = (uint2_t){pack_half2(v[k][0], v[k][1]), pack_half2(v[k][2], v[k][3])};
             else
                 *reinterpret_cast<float4_t *>(a.partials + (size_t)slice * a.M * a.N + out) = v[k];
         } else {
             const unsigned long long add = to_fixed(v[k][0]);
-            const unsigned long long total = __hip_atomic_fetch_add(acc + out, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+            const unsigned long long total = __hip_atomic_fetch_add(sync + out, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
             if ((total >> 56) == (unsigned long long)a.split) {
                 a.Y[out] = (uint16_t)(pack_half2(from_fixed(total), 0.f) & 0xFFFFu);
-                __hip_atomic_store(acc + out, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(sync + out, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }

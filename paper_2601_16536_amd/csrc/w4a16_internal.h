@@ -29,20 +29,36 @@ constexpr int kLdsBudget = 32768;   // bytes of LDS one workgroup stages X into
 hipError_t launch_mfma_reg(const GemmArgs &a, hipStream_t stream);
 hipError_t launch_wave_split(const GemmArgs &a, int tile_n, hipStream_t stream);
 hipError_t launch_mfma_rows(const GemmArgs &a, int tile_m, hipStream_t stream);
-// STRIPE family (M <= 16): `waves` waves per workgroup (stripe_min_waves .. stripe_max_waves).  With
-// split > 1 the K slices of different workgroups meet either in `acc`, the fixed-point accumulator [M,N]
-// of 64-bit words (all zero before and after every launch; split <= 255), or, when acc is null, in
-// a.partials (FP32 [S,M,N]) for the second pass.
-hipError_t launch_stripe(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream);
+// How the K slices of different workgroups meet (the scheduler's choice per shape).
+enum Finish : int {
+    kFinishDirect = 0,       // S = 1: the workgroup casts and stores Y
+    kFinishAccumulator = 1,  // one atomic add per output and slice into the fixed-point accumulator; the last arriver casts
+    kFinishSecondPass = 2    // FP32 partials [S, M, N], summed by the separate reduction kernel
+};
+
+// What a launch needs for its finish: S = 1 exactly when direct, the accumulator's count holds 255 slices.
+inline bool finish_args_ok(const GemmArgs &a, int finish, const unsigned long long *sync)
+{
+    switch (finish) {
+    case kFinishDirect: return a.split == 1;
+    case kFinishAccumulator: return a.split > 1 && a.split <= 255 && sync;
+    case kFinishSecondPass: return a.split > 1 && a.partials;
+    default: return false;
+    }
+}
+
+// STRIPE family (M <= 16): `waves` waves per workgroup (stripe_min_waves .. stripe_max_waves).  `finish`
+// says how the K slices of different workgroups meet; `sync` is the fixed-point accumulator [M, N] that
+// finish may need: 64-bit words, all zero before and after every launch.
+hipError_t launch_stripe(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream);
 size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves);  // LDS one workgroup needs
 int stripe_lds_limit();                                                       // most it may use
 int stripe_min_waves(int M);
 int stripe_max_waves(int M);
-// TILE family (the scheduler takes it for M >= 5): 64-column tiles, `rows_x` (16, 32 or 64) rows of X per workgroup,
-// `waves` (4..8) waves per workgroup that split the K slice; with split > 1 the slices meet in `acc`
-// or, when acc is null, in a.partials, as in the STRIPE family.
-hipError_t launch_tile(const GemmArgs &a, unsigned long long *acc, int rows_x, int waves, hipStream_t stream);
-size_t tile_lds_bytes(int rows_x, int waves);
+// TILE family (the scheduler takes it for M >= 5): 64-column tiles, `rows_x` (16, 32 or 64) rows of X per
+// workgroup, `waves` (4..8) waves per workgroup that split the K slice; `finish` and `sync` as in the STRIPE
+// family.
+hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, int waves, hipStream_t stream);
 // Clears n words of a fixed-point accumulator.
 hipError_t launch_accumulator_clear(unsigned long long *acc, size_t n, hipStream_t stream);
 // Second pass (Algorithm 1, Phase 3).

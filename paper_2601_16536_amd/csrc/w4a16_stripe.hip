@@ -83,7 +83,7 @@ struct Mma {
 };
 
 template <int MROWS>
-__global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const GemmArgs a, unsigned long long *__restrict__ acc, const int red_waves)
+__global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync, const int red_waves)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -283,16 +283,16 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
 #pragma unroll
         for (int i = 0; i < MROWS; ++i) mine[i * 64 + lane] = (float4_t){tot[0][i], tot[1][i], tot[2][i], tot[3][i]};
     };
-    if (a.split > 1 && !a.partials)
-        reduce_and_finish<MROWS, kStripe, 1, Mma<MROWS>::kMinWaves>(a, acc, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
+    if (finish == kFinishAccumulator)
+        reduce_and_finish<MROWS, kStripe, 1, Mma<MROWS>::kMinWaves>(a, finish, sync, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
     else
-        reduce_and_finish<MROWS, kStripe, 4, Mma<MROWS>::kMinWaves>(a, acc, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
+        reduce_and_finish<MROWS, kStripe, 4, Mma<MROWS>::kMinWaves>(a, finish, sync, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
 }
 
 int mrows_of(int M) { return M == 1 ? 1 : (M == 2 ? 2 : (M <= 4 ? 4 : (M <= 8 ? 8 : 16))); }
 
 template <int MROWS>
-hipError_t launch_m(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream)
+hipError_t launch_m(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
 {
     if (waves < Mma<MROWS>::kMinWaves || waves * 64 > Mma<MROWS>::kMaxThreads) return hipErrorInvalidValue;
     const size_t lds = stripe_lds_bytes(a.M, a.group, a.groups_per_split, waves);
@@ -308,7 +308,7 @@ hipError_t launch_m(const GemmArgs &a, unsigned long long *acc, int waves, hipSt
                                            hipFuncAttributeMaxDynamicSharedMemorySize, stripe_lds_limit());
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((stripe_kernel<MROWS>), dim3(nstripes * a.split), dim3(waves * 64), lds, stream, a, acc, red_waves);
+    hipLaunchKernelGGL((stripe_kernel<MROWS>), dim3(nstripes * a.split), dim3(waves * 64), lds, stream, a, finish, sync, red_waves);
     return hipGetLastError();
 }
 
@@ -340,21 +340,17 @@ size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves)
     return stage > red ? stage : red;
 }
 
-// `acc` != null: the slices meet in the fixed-point accumulator; else a.partials (FP32 [S, M, N]) takes them
-// and the caller runs the second pass.  Neither is used when a.split == 1.
-hipError_t launch_stripe(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream)
+// `finish` says how the slices meet (w4a16_finish.h); `sync` is the accumulator it may need.
+hipError_t launch_stripe(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
 {
     if (a.M > 16 || a.group % (8 * kBlockRows) != 0) return hipErrorInvalidValue;
-    if (a.split > 1 && !acc && !a.partials) return hipErrorInvalidValue;
-    if (a.split > 1 && acc && a.split > 255) return hipErrorInvalidValue;
-    GemmArgs b = a;
-    if (acc || a.split == 1) b.partials = nullptr;  // the kernel reads the finish mode off this pointer
+    if (!finish_args_ok(a, finish, sync)) return hipErrorInvalidValue;
     switch (mrows_of(a.M)) {
-    case 1: return launch_m<1>(b, acc, waves, stream);
-    case 2: return launch_m<2>(b, acc, waves, stream);
-    case 4: return launch_m<4>(b, acc, waves, stream);
-    case 8: return launch_m<8>(b, acc, waves, stream);
-    default: return launch_m<16>(b, acc, waves, stream);
+    case 1: return launch_m<1>(a, finish, sync, waves, stream);
+    case 2: return launch_m<2>(a, finish, sync, waves, stream);
+    case 4: return launch_m<4>(a, finish, sync, waves, stream);
+    case 8: return launch_m<8>(a, finish, sync, waves, stream);
+    default: return launch_m<16>(a, finish, sync, waves, stream);
     }
 }
 

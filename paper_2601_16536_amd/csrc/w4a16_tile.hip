@@ -51,7 +51,7 @@ struct Shape {
 };
 
 template <int RT>
-__global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, unsigned long long *__restrict__ acc, const int row_blocks, const int red_waves)
+__global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync, const int row_blocks, const int red_waves)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     typedef Shape<RT> Sh;
@@ -243,10 +243,10 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, unsigned lo
             for (int i = 0; i < 4; ++i)
                 mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = (float4_t){tot[rt][0][i], tot[rt][1][i], tot[rt][2][i], tot[rt][3][i]};
     };
-    if (a.split > 1 && !a.partials)
-        reduce_and_finish<Sh::kRowsX, kTileCols, 1, 4>(a, acc, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+    if (finish == kFinishAccumulator)
+        reduce_and_finish<Sh::kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
     else
-        reduce_and_finish<Sh::kRowsX, kTileCols, 4, 4>(a, acc, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+        reduce_and_finish<Sh::kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
 }
 
 // ---- group = 128: the waves' runs are whole quantisation groups ----
@@ -272,7 +272,7 @@ struct GroupShape {
 };
 
 template <int RT>
-__global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, unsigned long long *__restrict__ acc, const int row_blocks, const int red_waves)
+__global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync, const int row_blocks, const int red_waves)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     typedef GroupShape<RT> Sh;
@@ -357,6 +357,7 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, unsig
         for (int c = 0; c < 4; ++c) tot[rt][c] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
     if (ng > 0) {
+        const uint32_t zsh = (uint32_t)(col0 & 4) * 4u;  // this lane's four nibbles in its zero-point word
         // X of the first chunk goes ahead of the weights: loads return in order, and X (mostly cache hits)
         // must not queue behind the first weight blocks.
         x_load(0);
@@ -367,13 +368,12 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, unsig
         x_store(0);
 
         const uint32_t xa0 = (uint32_t)(wave * Sh::kWaveBytes + (g4 * Sh::kRowStride + j) * 16);  // A entry of block 0, row tile 0
-        const uint32_t zsh = (uint32_t)(col0 & 4) * 4u;  // this lane's four nibbles in its zero-point word
         const Masks masks = make_masks();
         // sum_k x_k over a group comes from the MFMA too: X against ones (16 where the staged x was divided by 16)
         const half8_t ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f, (_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f};
         const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
 
-        // One group: its four blocks from ring half H, chunk buffers by parity of the chunk number.  Only this
+        // One group: its four blocks from ring place R, chunk buffers by parity of the chunk number.  Only this
         // wave touches its LDS and the LDS operations of one wave complete in order; the fences only keep the
         // compiler from moving them across the staging.
         auto do_group = [&](auto half, const uint32_t gi) {
@@ -431,82 +431,102 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, unsig
             }
         };
 
-        for (uint32_t gi = 0; gi < (uint32_t)ng; gi += 2) {
-            do_group(std::integral_constant<int, 0>{}, gi);
-            if (gi + 1 < (uint32_t)ng) do_group(std::integral_constant<int, 1>{}, gi + 1);
+        // Ring places and chunk buffers are fixed per copy of the group's code: two copies where consecutive
+        // groups differ in either, one where they do not.
+        if constexpr (kRG == 2 || Sh::kChunks % 2 == 1) {
+            for (uint32_t gi = 0; gi < (uint32_t)ng; gi += 2) {
+                do_group(std::integral_constant<int, 0>{}, gi);
+                if (gi + 1 < (uint32_t)ng) do_group(std::integral_constant<int, 1>{}, gi + 1);
+            }
+        } else {
+            for (uint32_t gi = 0; gi < (uint32_t)ng; ++gi) do_group(std::integral_constant<int, 0>{}, gi);
         }
     }
 
-    // Phase 3 inside the workgroup, then across workgroups (see w4a16_finish.h).
+    // Phase 3 inside the workgroup, then across workgroups (see w4a16_finish.h).  The sums are regrouped
+    // here, once, into the four neighbouring columns a lane hands over per row.
+    float4_t mine4[RT][4];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mine4[rt][i] = (float4_t){tot[rt][0][i], tot[rt][1][i], tot[rt][2][i], tot[rt][3][i]};
     const auto write_mine = [&](float4_t *mine) {  // [row][column / 4] of the 64-column tile
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = (float4_t){tot[rt][0][i], tot[rt][1][i], tot[rt][2][i], tot[rt][3][i]};
+            for (int i = 0; i < 4; ++i) mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = mine4[rt][i];
     };
-    if (a.split > 1 && !a.partials)
-        reduce_and_finish<Sh::kRowsX, kTileCols, 1, 4>(a, acc, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+    if (finish == kFinishAccumulator)
+        reduce_and_finish<Sh::kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
     else
-        reduce_and_finish<Sh::kRowsX, kTileCols, 4, 4>(a, acc, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+        reduce_and_finish<Sh::kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
 }
 
+// The waves' chunk buffers; the final sums reuse the space, a whole number of waves' tiles per round.
 size_t lds_bytes(int rows_x, int waves, bool by_group)
 {
     const size_t wave_bytes = by_group ? (rows_x == 16 ? GroupShape<1>::kWaveBytes : rows_x == 32 ? GroupShape<2>::kWaveBytes : GroupShape<4>::kWaveBytes)
                                        : (rows_x == 16 ? Shape<1>::kWaveBytes : rows_x == 32 ? Shape<2>::kWaveBytes : Shape<4>::kWaveBytes);
     const size_t stage = (size_t)waves * wave_bytes;
-    // the final sums reuse the space, a whole number of waves' tiles per round
     const size_t one = (size_t)rows_x * kTileCols * 4;
     size_t red = one * waves;
     if (red > 64 * 1024) red = 64 * 1024 / one * one;
     return stage > red ? stage : red;
 }
 
-template <int RT>
-hipError_t launch_rt(const GemmArgs &a, unsigned long long *acc, int waves, hipStream_t stream)
+struct Launch {
+    int grid, row_blocks, red_waves;
+    size_t lds;
+};
+
+// Grid and LDS of a launch; false if the shape is beyond the kernels' 32-bit offsets.
+bool prepare(const GemmArgs &a, int rows_x, int waves, bool by_group, Launch *l)
 {
-    typedef Shape<RT> Sh;
-    const bool by_group = a.group == 128;
-    const size_t lds = lds_bytes(Sh::kRowsX, waves, by_group);
-    int red_waves = (int)(lds / Sh::kOutBytes);
-    if (red_waves < 1) return hipErrorInvalidValue;
-    if (red_waves > waves) red_waves = waves;
+    l->lds = lds_bytes(rows_x, waves, by_group);
+    l->red_waves = (int)(l->lds / ((size_t)rows_x * kTileCols * 4));
+    if (l->red_waves < 1) return false;
+    if (l->red_waves > waves) l->red_waves = waves;
     const unsigned long long rows = (unsigned long long)a.groups_per_split * (a.group / 8);
-    if (rows * a.N * 4ull >= 0x7F000000ull) return hipErrorInvalidValue;  // slice-relative 32-bit buffer offsets
-    if ((unsigned long long)a.M * a.K * 2ull >= 0x7F000000ull) return hipErrorInvalidValue;
+    if (rows * a.N * 4ull >= 0x7F000000ull) return false;  // slice-relative 32-bit buffer offsets
+    if ((unsigned long long)a.M * a.K * 2ull >= 0x7F000000ull) return false;
     const int ntiles = (a.N + kTileCols - 1) / kTileCols;
-    const int row_blocks = (a.M + Sh::kRowsX - 1) / Sh::kRowsX;
+    l->row_blocks = (a.M + rows_x - 1) / rows_x;
     const long long units = (long long)ntiles * a.split;
-    const long long grid = (units + kXcds - 1) / kXcds * kXcds * row_blocks;
-    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
-    const void *fn = by_group ? reinterpret_cast<const void *>(&tile_group_kernel<RT>) : reinterpret_cast<const void *>(&tile_kernel<RT>);
-    if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const long long grid = (units + kXcds - 1) / kXcds * kXcds * l->row_blocks;
+    if (grid > 0x7FFFFFFF) return false;
+    l->grid = (int)grid;
+    return true;
+}
+
+template <typename Kernel>
+hipError_t launch_kernel(Kernel kernel, const Launch &l, const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
+{
+    if (l.lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)l.lds);
         if (e != hipSuccess) return e;
     }
-    if (by_group)
-        hipLaunchKernelGGL((tile_group_kernel<RT>), dim3((unsigned)grid), dim3(waves * 64), lds, stream, a, acc, row_blocks, red_waves);
-    else
-        hipLaunchKernelGGL((tile_kernel<RT>), dim3((unsigned)grid), dim3(waves * 64), lds, stream, a, acc, row_blocks, red_waves);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)l.grid), dim3(waves * 64), l.lds, stream, a, finish, sync, l.row_blocks, l.red_waves);
     return hipGetLastError();
 }
 
 }  // namespace
 
-size_t tile_lds_bytes(int rows_x, int waves) { return lds_bytes(rows_x, waves, true); }
-
-hipError_t launch_tile(const GemmArgs &a, unsigned long long *acc, int rows_x, int waves, hipStream_t stream)
+hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, int waves, hipStream_t stream)
 {
     if (waves < 4 || waves > 8 || a.group % (8 * kBlockRows) != 0) return hipErrorInvalidValue;
-    if (a.split > 1 && !acc && !a.partials) return hipErrorInvalidValue;
-    if (a.split > 1 && acc && a.split > 255) return hipErrorInvalidValue;
-    GemmArgs b = a;
-    if (acc || a.split == 1) b.partials = nullptr;  // the kernel reads the finish mode off this pointer
-    if (rows_x == 16) return launch_rt<1>(b, acc, waves, stream);
-    if (rows_x == 32) return launch_rt<2>(b, acc, waves, stream);
-    if (rows_x == 64) return launch_rt<4>(b, acc, waves, stream);
-    return hipErrorInvalidValue;
+    if (rows_x != 16 && rows_x != 32 && rows_x != 64) return hipErrorInvalidValue;
+    if (!finish_args_ok(a, finish, sync)) return hipErrorInvalidValue;
+    const bool by_group = a.group == 128;
+    Launch l;
+    if (!prepare(a, rows_x, waves, by_group, &l)) return hipErrorInvalidValue;
+    if (by_group) {
+        if (rows_x == 16) return launch_kernel(&tile_group_kernel<1>, l, a, finish, sync, waves, stream);
+        if (rows_x == 32) return launch_kernel(&tile_group_kernel<2>, l, a, finish, sync, waves, stream);
+        return launch_kernel(&tile_group_kernel<4>, l, a, finish, sync, waves, stream);
+    }
+    if (rows_x == 16) return launch_kernel(&tile_kernel<1>, l, a, finish, sync, waves, stream);
+    if (rows_x == 32) return launch_kernel(&tile_kernel<2>, l, a, finish, sync, waves, stream);
+    return launch_kernel(&tile_kernel<4>, l, a, finish, sync, waves, stream);
 }
 
 }  // namespace w4a16

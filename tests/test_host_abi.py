@@ -87,9 +87,11 @@ def test_plans_are_well_formed(binding, M, N, K):
             if split:
                 assert S <= split
             stripe = p["kernel"] == binding.KERNEL_STRIPE
-            # STRIPE and TILE slices meet in the 64-bit accumulator while the adds are few
+            # STRIPE and TILE slices meet in the 64-bit accumulator while the adds are few; else, and in
+            # the other families, FP32 partials go to the second pass
             in_acc = p["kernel"] in (binding.KERNEL_STRIPE, binding.KERNEL_TILE) and S <= 255 and S * M * N <= 640 * 1024
-            assert p["workspace_bytes"] == ((M * N * 8 if in_acc else S * M * N * 4) if S > 1 else 0)
+            want = 0 if S == 1 else (M * N * 8 if in_acc else S * M * N * 4)
+            assert p["workspace_bytes"] == want
             assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (3 if M <= 4 else 4))
             tiles_n = -(-N // p["tile_n"])
             tiles_m = -(-M // p["tile_m"]) if p["kernel"] not in (binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE) else 1
