@@ -360,12 +360,14 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
         const uint32_t zsh = (uint32_t)(col0 & 4) * 4u;  // this lane's four nibbles in its zero-point word
         // X of the first chunk goes ahead of the weights: loads return in order, and X (mostly cache hits)
         // must not queue behind the first weight blocks.
+        const uint32_t nchunks = (uint32_t)ng * Sh::kChunks;
         x_load(0);
 #pragma unroll
         for (int h = 0; h < kRG; ++h)
 #pragma unroll
             for (int p = 0; p < kBpg; ++p) load_w(wq[h * kBpg + p]);
         x_store(0);
+        if (nchunks > 1) x_load(1);
 
         const uint32_t xa0 = (uint32_t)(wave * Sh::kWaveBytes + (g4 * Sh::kRowStride + j) * 16);  // A entry of block 0, row tile 0
         const Masks masks = make_masks();
@@ -391,8 +393,6 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
                 constexpr int CB = Sh::kChunkBlocks;
                 const int c = p / CB, lb = p % CB;
                 const int par = (H * Sh::kChunks + c) & 1;
-                const bool more = c + 1 < Sh::kChunks || gi + 1 < (uint32_t)ng;  // a chunk follows this one
-                if (lb == 0 && more) x_load(gi * Sh::kChunks + c + 1);
                 const unsigned char *xb = smem + xa0 + par * Sh::kBufBytes + lb * (kBlockRows * Sh::kRowStride * 16);
                 half8_t bop[4];
 #pragma unroll
@@ -406,12 +406,19 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
                         part[rt][cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, bop[cc], p == 0 ? zero4 : part[rt][cc], 0, 0, 0);
                     xsum[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, ones, p == 0 ? zero4 : xsum[rt], 0, 0, 0);
                 }
-                load_w(wq[R * kBpg + p]);  // the same block kRG groups on
-                if (lb == CB - 1 && more) {
-                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                    x_store(par ^ 1);
-                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                if (lb == CB - 1) {
+                    // The chunk is done.  Its successor's X, asked for a chunk ago, goes to the other buffer, and
+                    // the chunk after that is asked for: ahead of the weight load below, because loads return in
+                    // order and waiting for X must not mean waiting for weights wanted much later.
+                    const uint32_t n = gi * Sh::kChunks + c;  // this chunk of the run
+                    if (n + 1 < nchunks) {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                        x_store(par ^ 1);
+                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    }
+                    if (n + 2 < nchunks) x_load(n + 2);
                 }
+                load_w(wq[R * kBpg + p]);  // the same block kRG groups on
             }
             // the group is done: scale and zero point (Eq. 2)
             H2 s01, s23;
