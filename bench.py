@@ -2,7 +2,7 @@
 """Benchmark of the W4A16 GEMM hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
-                    [--config c4] [--M 1] [--kernel -1] [--split 0] [--warm] [--table]
+                    [--config c4] [--M 1] [--kernel -1] [--split 0] [--warm] [--table] [--fig2]
 
 A step is one whole GEMM (Eq. 2: every launch w4a16_gemm enqueues for it) on
 seeded synthetic inputs already resident in HBM.  By default consecutive steps
@@ -52,7 +52,7 @@ def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, wa
               replays=3):
     """Returns dict with µs per GEMM: HIP events around `steps` back-to-back GEMMs (one replay of a HIP graph
     that holds them, best of `replays`; graph=False times the eager Python loop instead)."""
-    cfg = wl.CONFIGS[name]
+    cfg = wl.config(name)
     if host is None:
         host = wl.make_config(name)
     Xall, Wp, s, Zp = host
@@ -131,6 +131,35 @@ def cpu_baseline(wl, orc, host, M, cfg):
     }, ref
 
 
+def fig2(torch, binding, wl, max_steps):
+    """Section 4.1's comparison on this GPU: the scheduler's plan (Split-K where it pays) against the
+    data-parallel plans, i.e. S = 1 forced on each kernel family that takes the shape: column tiles spread
+    over the workgroups, K not split between them.  The baseline is the fastest of those."""
+    rows = []
+    for name, c in wl.FIG2.items():
+        h = wl.make_config(name)
+        steps = max(50, min(max_steps, int(2e5 / max(1.0, 1e-6 * c.K * c.N / 16))))
+        for M in c.Ms:
+            auto, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), host=h)
+            dp = {}
+            for fam, kid in (("wave_split", binding.KERNEL_WAVE_SPLIT), ("stripe", binding.KERNEL_STRIPE),
+                             ("tile", binding.KERNEL_TILE), ("mfma_rows", binding.KERNEL_MFMA_ROWS)):
+                if (kid == binding.KERNEL_WAVE_SPLIT and M > 4) or (kid == binding.KERNEL_STRIPE and M > 16):
+                    continue
+                if binding.query_plan(M, c.N, c.K, c.group, kid, 1)["split"] != 1:
+                    continue  # the family cannot take the whole K in one slice here
+                r, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), kernel=kid, split=1, host=h)
+                dp[fam] = r["us_per_gemm"]
+            best = min(dp, key=dp.get)
+            row = {"shape": name, "N": c.N, "K": c.K, "M": M, "split_k_us": auto["us_per_gemm"],
+                   "split_k_plan": auto["plan"], "data_parallel_us": dp, "data_parallel_best": best,
+                   "speedup": dp[best] / auto["us_per_gemm"]}
+            log(json.dumps(row))
+            rows.append(row)
+        del h
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -142,6 +171,9 @@ def main():
     ap.add_argument("--split", type=int, default=0)
     ap.add_argument("--warm", action="store_true")
     ap.add_argument("--table", action="store_true")
+    ap.add_argument("--fig2", action="store_true",
+                    help="also time Split-K (the scheduler's plan) against data-parallel plans (S = 1) on the "
+                         "(N, K) pairs of the paper's Fig. 2")
     ap.add_argument("--no-cpu", action="store_true", help="skip the host-baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -205,6 +237,11 @@ def main():
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
             json.dump(line, f, indent=1)
+    if args.fig2:
+        line["fig2"] = fig2(torch, binding, wl, args.steps)
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_fig2.json"), "w") as f:
+            json.dump(line["fig2"], f, indent=1)
     print(json.dumps(line), flush=True)
 
 

@@ -75,10 +75,12 @@ typedef enum {
     W4A16_KERNEL_MFMA_REG = 1,   /* any M: 256-column tiles, weights unpacked straight into MFMA operand registers */
     W4A16_KERNEL_MFMA_ROWS = 2,  /* any M, meant for M > 16: as MFMA_REG with 32 or 64 rows of X staged in LDS per
                                     workgroup, every unpacked weight word reused over the row tiles               */
-    W4A16_KERNEL_STRIPE = 3,     /* M <= 16, the scheduler's choice for M <= 4: 256-column stripe x K slice per workgroup, its waves own contiguous runs
-                                    of the slice (LDS reduction); slices of different workgroups meet in a 64-bit
-                                    fixed-point accumulator by one atomic add each, no second launch              */
-    W4A16_KERNEL_TILE = 4        /* any M, the scheduler's choice for M >= 5: 64-column tile x 16, 32 or 64 rows of X
+    W4A16_KERNEL_STRIPE = 3,     /* M <= 16; the scheduler's choice for M <= 2 (M <= 4) from about 10 MB (48 MB) of
+                                    packed weights on: 256-column stripe x K slice per workgroup, its waves own
+                                    contiguous runs of the slice (LDS reduction); slices of different workgroups
+                                    meet in a 64-bit fixed-point accumulator by one atomic add each, no second
+                                    launch                                                                        */
+    W4A16_KERNEL_TILE = 4        /* any M, the scheduler's choice otherwise: 64-column tile x 16, 32 or 64 rows of X
                                     per workgroup, its waves own contiguous runs of K (LDS reduction), plain MFMA
                                     operand layout; slices of different workgroups meet as in STRIPE                */
 } w4a16_kernel;

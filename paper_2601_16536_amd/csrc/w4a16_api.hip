@@ -77,14 +77,13 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // Algorithm 1 takes the split factor S and the block sizes as inputs.  Here the
 // scheduler (kernel = AUTO, split = 0) chooses them from the shape alone:
 //
-// M <= 4 (STRIPE): 256-column stripes x S slices of K with S = compute units /
-//   stripes, so that one workgroup runs per compute unit; ten to sixteen waves of
-//   a workgroup own contiguous runs of the slice's rows.
-// M >= 5 (TILE): 64-column tiles x 16, 32 or 64 rows of X per workgroup (as many
-//   rows as still leave a workgroup per compute unit at S = 1), eight waves own
-//   contiguous runs of the slice's K; S again fills the compute units.
-//   Measured crossover at K = 14336, N = 4096: STRIPE 8.7 / 9.1 / 10.8 us at
-//   M = 1 / 2 / 4, TILE 10.6 - 10.7 us for every M <= 16, STRIPE 12.0 us at M = 5.
+// STRIPE (M <= 2 from about 10 MB of packed weights on, M <= 4 from about 48 MB on): 256-column stripes
+//   x S slices of K with S = compute units / stripes, so that one workgroup runs per compute unit; ten
+//   to sixteen waves of a workgroup own contiguous runs of the slice's rows.
+// TILE (everything else): 64-column tiles x 16, 32 or 64 rows of X per workgroup (as many rows as still
+//   leave a workgroup per compute unit at S = 1), eight waves own contiguous runs of the slice's K;
+//   S = compute units / workgroups, rounded down (a workgroup too many would run as a second round).
+//   Its time does not depend on M up to 16; STRIPE's grows with the S M N atomic adds of its finish.
 //
 // The families below are kept as forced plans (w4a16_gemm_ex) for comparison:
 // WAVE_SPLIT (M <= 4): one workgroup of sixteen waves per column tile of 32 or
@@ -130,8 +129,15 @@ size_t workspace_of(int kernel, int M, int N, int S)
 int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4a16_plan *p)
 {
     const int G = K / group;
-    if (kernel == W4A16_KERNEL_AUTO)
-        kernel = M <= 4 ? W4A16_KERNEL_STRIPE : W4A16_KERNEL_TILE;  // measured crossover (K = 14336, N = 4096): M = 4
+    if (kernel == W4A16_KERNEL_AUTO) {
+        // STRIPE streams large weight matrices about 8 % faster than TILE, but its 256-column stripes need four
+        // times the slices, hence four times the atomic adds (S M N), and it carries more fixed cost.
+        // Measured on sixteen shapes from 2 MB to 117 MB of packed weights: STRIPE wins for M <= 2 from about
+        // 10 MB on, for M = 3, 4 only from about 48 MB on; TILE everywhere else.
+        const double packed = 0.5 * (double)K * (double)N;
+        const bool stripe = (M <= 2 && packed >= 10e6) || (M <= 4 && packed >= 48e6);
+        kernel = stripe ? W4A16_KERNEL_STRIPE : W4A16_KERNEL_TILE;
+    }
     if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG && kernel != W4A16_KERNEL_MFMA_ROWS &&
         kernel != W4A16_KERNEL_STRIPE && kernel != W4A16_KERNEL_TILE)
         return W4A16_ERR_UNSUPPORTED;
@@ -195,7 +201,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
             if (w >= 4 && w <= 8) { p->waves_k = w; p->threads = 64 * w; }
         }
         const long long wgs = tiles * ((M + rows_x - 1) / rows_x);
-        if (S == 0) S = (int)((cus + wgs / 2) / wgs);
+        if (S == 0) S = (int)(cus / wgs);  // never more workgroups than compute units: the extra ones would run as a second round
         if (S < 1) S = 1;
         if (S > G) S = G;
         int gps = (G + S - 1) / S;

@@ -48,6 +48,23 @@ CONFIGS = {
 }
 
 
+# The (N, K) pairs of the paper's Split-K against data-parallel comparison (Section 4.1, Fig. 2, panels a to f;
+# panel d prints K = 16348, read as 16384), with the batch sizes of a decode server.
+FIG2_MS = (1, 2, 4, 8, 16, 32, 64)
+FIG2 = {
+    "f2a": Config("f2a", 21, 6144, 1536, FIG2_MS),
+    "f2b": Config("f2b", 22, 8192, 2048, FIG2_MS),
+    "f2c": Config("f2c", 23, 10240, 2048, FIG2_MS),
+    "f2d": Config("f2d", 24, 16384, 4096, FIG2_MS),
+    "f2e": Config("f2e", 25, 10240, 4608, FIG2_MS),
+    "f2f": Config("f2f", 26, 18432, 7168, FIG2_MS),
+}
+
+
+def config(name: str) -> Config:
+    return CONFIGS[name] if name in CONFIGS else FIG2[name]
+
+
 def pack_along_k(q: np.ndarray) -> np.ndarray:
     """codes q[K, N] in 0..15 -> Wp[K/8, N] uint32 (layout only)."""
     q = np.asarray(q)
@@ -112,7 +129,7 @@ def make(M: int, K: int, N: int, index: int, group: int = GROUP, outliers: bool 
 def make_config(name: str, M: int | None = None):
     """Inputs of a named configuration; X has max(Ms) rows unless M is given
     (then the leading M rows of that same draw)."""
-    c = CONFIGS[name]
+    c = config(name)
     Mmax = max(c.Ms)
     X, Wp, scales, Zp = make(Mmax, c.K, c.N, c.index, c.group, c.outliers)
     if M is not None:

@@ -362,3 +362,29 @@ def test_baseline_configs_full_size(gpu, name):
         torch.cuda.synchronize()
         d = np.abs(Y2.cpu().numpy().astype(np.float64) - out.astype(np.float64))
         assert np.max(d / (1 + np.abs(out.astype(np.float64)))) < 4e-3
+
+
+@pytest.mark.parametrize("name", sorted(wl.FIG2))
+def test_fig2_shapes_split_k_and_data_parallel(gpu, name):
+    """The (N, K) pairs of the paper's Split-K against data-parallel comparison
+    (Section 4.1, Fig. 2), as bench.py --fig2 times them: the scheduler's plan
+    and the S = 1 plan of the TILE family, on all rows of sampled columns."""
+    torch, binding = gpu
+    cfg = wl.FIG2[name]
+    Xall, Wp, s, Zp = wl.make_config(name)
+    dW, dS, dZ = [t for t in binding.to_device(Xall, Wp, s, Zp)[1:]]
+    for M in (1, 4, 16, 64):
+        X = np.ascontiguousarray(Xall[:M])
+        cols = _sample_cols(cfg.N, 96, seed=100 + M)
+        ref = orc.gemm(X, Wp, s, Zp, cfg.group, cols=cols)
+        dX = torch.from_numpy(X).cuda()
+        for kernel, split in ((binding.KERNEL_AUTO, 0), (binding.KERNEL_TILE, 1)):
+            say(name, "M", M, binding.query_plan(M, cfg.N, cfg.K, cfg.group, kernel, split))
+            Y = torch.full((M, cfg.N), float("nan"), dtype=torch.float16, device="cuda")
+            binding.gemm_ex(dX, dW, dS, dZ, cfg.group, kernel=kernel, split=split, out=Y)
+            torch.cuda.synchronize()
+            out = Y.cpu().numpy()
+            assert np.isfinite(out).all()
+            r = err_ratio(out[:, cols], ref)
+            print("   err/tol = %.4f" % r, flush=True)
+            assert r <= 1.0, (name, M, kernel, split, r)

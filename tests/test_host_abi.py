@@ -92,7 +92,9 @@ def test_plans_are_well_formed(binding, M, N, K):
             in_acc = p["kernel"] in (binding.KERNEL_STRIPE, binding.KERNEL_TILE) and S <= 255 and S * M * N <= 640 * 1024
             want = 0 if S == 1 else (M * N * 8 if in_acc else S * M * N * 4)
             assert p["workspace_bytes"] == want
-            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else (3 if M <= 4 else 4))
+            packed = 0.5 * K * N  # bytes of packed weights: the scheduler's STRIPE / TILE rule
+            auto = 3 if (M <= 2 and packed >= 10e6) or (M <= 4 and packed >= 48e6) else 4
+            assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else auto)
             tiles_n = -(-N // p["tile_n"])
             tiles_m = -(-M // p["tile_m"]) if p["kernel"] not in (binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE) else 1
             assert p["workgroups"] == tiles_n * tiles_m * S
