@@ -89,6 +89,30 @@ def test_small_shapes_every_split(gpu, M, K, N, group):
             assert r <= 1.0, (M, K, N, group, kernel, split, r)
 
 
+@pytest.mark.parametrize("rows_x", [16, 32, 64])
+def test_tile_family_every_row_block(gpu, rows_x, monkeypatch):
+    """The TILE kernels for 16, 32 and 64 rows of X per workgroup.  The scheduler takes the larger blocks
+    only where N is large, so the library's tuning variable forces them here on small ragged shapes
+    (rows past M, columns past N, fewer groups than waves, group sizes with and without the
+    group-aligned loop)."""
+    _, binding = gpu
+    monkeypatch.setenv("W4A16_TILE_ROWS", str(rows_x))
+    for (M, K, N, group) in [(33, 640, 72, 128), (130, 512, 136, 128), (200, 1024, 200, 128), (40, 256, 64, 128),
+                             (64, 2048, 520, 128), (7, 128, 64, 128), (70, 768, 264, 64), (129, 1024, 72, 256)]:
+        X, Wp, s, Zp = wl.make(M, K, N, index=2000 + M + K + N, group=group)
+        ref = orc.gemm(X, Wp, s, Zp, group)
+        G = K // group
+        for split in sorted({0, 1, 2, 3, G}):
+            if split > G:
+                continue
+            plan = binding.query_plan(M, N, K, group, binding.KERNEL_TILE, split)
+            assert plan["tile_m"] == rows_x
+            say("tile rows", rows_x, (M, K, N, group), "split", split, plan)
+            Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=binding.KERNEL_TILE, split=split)
+            r = err_ratio(Y, ref)
+            assert r <= 1.0, (rows_x, M, K, N, group, split, r)
+
+
 def test_integer_case_bit_exact(gpu):
     """s = 1, z = 0, X in {-1,0,1}, K = 128: integers below 2048, exactly representable."""
     rng = np.random.default_rng(21)
