@@ -2,7 +2,7 @@
 """Benchmark of the W4A16 GEMM hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
-                    [--config c4] [--M 1] [--kernel -1] [--split 0] [--warm] [--table] [--fig2]
+                    [--config c4] [--M 1] [--kernel -1] [--split 0] [--warm] [--table] [--fig2] [--ablation]
 
 A step is one whole GEMM (Eq. 2: every launch w4a16_gemm enqueues for it) on
 seeded synthetic inputs already resident in HBM.  By default consecutive steps
@@ -160,6 +160,73 @@ def fig2(torch, binding, wl, max_steps):
     return rows
 
 
+def time_calls(torch, fn, steps, warmup, replays=3):
+    """us per call of fn(i): HIP events around one replay of a HIP graph holding `steps` calls; the eager
+    loop where the calls cannot be captured."""
+    stream = torch.cuda.current_stream()
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    try:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(steps):
+                fn(warmup + i)
+        run = g.replay
+    except Exception as e:  # a library call that refuses capture
+        log("graph capture refused (%s): timing the eager loop" % e)
+        torch.cuda.synchronize()
+
+        def run():
+            for i in range(steps):
+                fn(warmup + i)
+    run()
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(replays):
+        e0.record(stream)
+        run()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    return best * 1e3 / steps
+
+
+def ablation(torch, binding, wl, max_steps):
+    """Section 4.2 on this GPU.  Unfused: Phase 1 writes the dequantised FP16 weights to global memory
+    (w4a16_dequant), an FP16 GEMM (torch.matmul, i.e. the vendor BLAS) reads them back.  FP16 x FP16: that
+    GEMM alone, the weights never quantised.  Fused: w4a16_gemm.  Cold: consecutive steps use different
+    copies of the weights (FP16 copies of 100 MB and more are rotated in pairs: one pass already
+    exceeds the 256 MB last-level cache together with its successor)."""
+    rows = []
+    for name, Ms in (("c2", (1,)), ("c3", (1, 16)), ("c4", (1, 8)), ("c5", (32, 128))):
+        cfg = wl.config(name)
+        host = wl.make_config(name)
+        Xall, Wp, s, Zp = host
+        dW, dS, dZ = binding.to_device(Xall[:1], Wp, s, Zp)[1:]
+        fp16_bytes = 2 * cfg.K * cfg.N
+        copies = max(2, -(-COLD_BYTES // fp16_bytes))
+        W16 = [binding.dequant(dW, dS, dZ, cfg.group) for _ in range(copies)]
+        steps = max(30, min(max_steps, int(5e4 / max(1.0, 1e-6 * cfg.K * cfg.N / 16))))
+        t_deq = time_calls(torch, lambda i: binding.dequant(dW, dS, dZ, cfg.group, out=W16[i % copies]), steps, 5)
+        for M in Ms:
+            dX = torch.from_numpy(np.ascontiguousarray(Xall[:M])).cuda()
+            Y = torch.empty((M, cfg.N), dtype=torch.float16, device="cuda")
+            t_mm = time_calls(torch, lambda i: torch.matmul(dX, W16[i % copies], out=Y), steps, 5)
+            fused, Yf, _ = time_gemm(torch, binding, wl, name, M, steps, 10, host=host)
+            d = (Y.float() - Yf.float()).abs().max().item()  # same product up to the FP16 rounding of the weights
+            row = {"config": name, "M": M, "K": cfg.K, "N": cfg.N, "fused_us": fused["us_per_gemm"], "dequant_us": t_deq,
+                   "fp16_gemm_us": t_mm, "unfused_us": t_deq + t_mm, "unfused_over_fused": (t_deq + t_mm) / fused["us_per_gemm"],
+                   "fp16_over_fused": t_mm / fused["us_per_gemm"], "max_abs_diff_unfused_vs_fused": d}
+            log(json.dumps(row))
+            rows.append(row)
+        del W16
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -174,6 +241,9 @@ def main():
     ap.add_argument("--fig2", action="store_true",
                     help="also time Split-K (the scheduler's plan) against data-parallel plans (S = 1) on the "
                          "(N, K) pairs of the paper's Fig. 2")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the unfused variant (dequantised FP16 weights through HBM + vendor FP16 GEMM) "
+                         "and the FP16 x FP16 GEMM alone against the fused path (Section 4.2)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the host-baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -237,6 +307,11 @@ def main():
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
             json.dump(line, f, indent=1)
+    if args.ablation:
+        line["ablation"] = ablation(torch, binding, wl, args.steps)
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_ablation.json"), "w") as f:
+            json.dump(line["ablation"], f, indent=1)
     if args.fig2:
         line["fig2"] = fig2(torch, binding, wl, args.steps)
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)

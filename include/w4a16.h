@@ -137,6 +137,14 @@ int w4a16_query_plan(int M, int N, int K, int group, int kernel, int split, w4a1
  * i ascending, FP32 adds, round-to-nearest-even cast.  partials: FP32 [S, M, N]. */
 int w4a16_reduce(const float *partials, int S, int M, int N, void *Y, void *stream);
 
+/* Phase 1 alone (Algorithm 1; Eq. 2): W16[k,n] = fp16(scales[k/group, n] * (q[k,n] - z[k/group, n])), one
+ * round-to-nearest-even cast of the exact FP32 product.  W16: device pointer, FP16 [K, N] row-major, 16-byte
+ * aligned, owned by the caller, fully overwritten.  w4a16_gemm never materialises this matrix; the entry point
+ * serves the unfused variant that Section 4.2 diagnoses (FP16 weights through global memory, then an FP16 GEMM),
+ * which the benchmark times beside the fused path.  Same shape rules and error codes as w4a16_gemm. */
+int w4a16_dequant(const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int N, int K,
+                  void *W16, void *stream);
+
 /* Text for a status code (static storage). */
 const char *w4a16_status_string(int status);
 

@@ -17,7 +17,7 @@ KERNEL_AUTO, KERNEL_WAVE_SPLIT, KERNEL_MFMA_REG, KERNEL_MFMA_ROWS, KERNEL_STRIPE
 
 EXPORTS = (
     "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_workspace_bytes", "w4a16_query_plan",
-    "w4a16_reduce", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
+    "w4a16_reduce", "w4a16_dequant", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
 )
 
 
@@ -67,6 +67,7 @@ def lib():
         L.w4a16_workspace_bytes.restype = sz
         L.w4a16_query_plan.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(Plan)]
         L.w4a16_reduce.argtypes = [vp, ci, ci, ci, vp, vp]
+        L.w4a16_dequant.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp]
         L.w4a16_status_string.argtypes = [ci]
         L.w4a16_status_string.restype = ctypes.c_char_p
         L.w4a16_last_hip_error.argtypes = []
@@ -183,6 +184,26 @@ def reduce(partials, out=None, stream=None):
     if rc:
         raise W4A16Error(rc, "w4a16_reduce")
     return Y
+
+
+def dequant(Wpacked, scales, zeros, group: int, out=None, stream=None):
+    """Phase 1 alone (Algorithm 1): the FP16 matrix [K, N] of dequantised weights, for the unfused variant."""
+    import torch
+    if not (Wpacked.is_cuda and scales.is_cuda and zeros.is_cuda):
+        raise TypeError("device tensors wanted")
+    if Wpacked.dtype != torch.int32 or zeros.dtype != torch.int32 or scales.dtype != torch.float16:
+        raise TypeError("Wpacked and zeros are int32 (uint32 bits), scales float16")
+    if not (Wpacked.is_contiguous() and scales.is_contiguous() and zeros.is_contiguous()):
+        raise TypeError("contiguous tensors wanted")
+    K, N = Wpacked.shape[0] * 8, Wpacked.shape[1]
+    if K % group or tuple(scales.shape) != (K // group, N) or tuple(zeros.shape) != (K // group, N // 8):
+        raise W4A16Error(2, "binding.dequant (shapes of scales / zeros)")
+    W16 = out if out is not None else torch.empty((K, N), dtype=torch.float16, device=Wpacked.device)
+    rc = lib().w4a16_dequant(Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, N, K, W16.data_ptr(),
+                             _stream(stream))
+    if rc:
+        raise W4A16Error(rc, "w4a16_dequant")
+    return W16
 
 
 def shutdown() -> None:

@@ -423,6 +423,20 @@ int w4a16_reduce(const float *partials, int S, int M, int N, void *Y, void *stre
     return W4A16_OK;
 }
 
+int w4a16_dequant(const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int N, int K,
+                  void *W16, void *stream)
+{
+    t_hip_error[0] = 0;
+    if (!Wpacked || !scales || !zeros || !W16) return W4A16_ERR_NULL;
+    int rc = check_shape(group, 1, N, K);
+    if (rc) return rc;
+    if (!aligned16(Wpacked) || !aligned16(scales) || !aligned16(zeros) || !aligned16(W16)) return W4A16_ERR_ALIGN;
+    hipError_t e = launch_dequant(Wpacked, static_cast<const uint16_t *>(scales), zeros, group, N, K,
+                                  static_cast<uint16_t *>(W16), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+    return W4A16_OK;
+}
+
 const char *w4a16_status_string(int status)
 {
     switch (status) {

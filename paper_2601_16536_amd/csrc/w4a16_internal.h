@@ -61,6 +61,9 @@ int stripe_max_waves(int M);
 hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, int waves, hipStream_t stream);
 // Clears n words of a fixed-point accumulator.
 hipError_t launch_accumulator_clear(unsigned long long *acc, size_t n, hipStream_t stream);
+// Phase 1 alone (Algorithm 1): W16[K, N] = fp16(s (q - z)) in global memory, for the unfused variant.
+hipError_t launch_dequant(const uint32_t *Wp, const uint16_t *scales, const uint32_t *Zp, int group, int N, int K,
+                          uint16_t *W16, hipStream_t stream);
 // Second pass (Algorithm 1, Phase 3).
 hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream);
 

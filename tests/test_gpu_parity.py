@@ -338,6 +338,22 @@ def test_reduce_entry_point(gpu):
     assert np.array_equal(Y.cpu().numpy(), acc.astype(np.float16))
 
 
+def test_dequant_entry_point_bit_exact(gpu):
+    """Phase 1 alone: fp16(s (q - z)), one rounding of an exact FP32 product - bit for bit the oracle's
+    dequantised weights rounded to FP16 (ragged N, several group sizes, every nibble and zero-point position)."""
+    torch, binding = gpu
+    for (K, N, group) in [(128, 8, 128), (256, 264, 128), (1024, 72, 64), (384, 136, 32), (2304, 1000, 128), (4096, 4104, 128)]:
+        _, Wp, s, Zp = wl.make(1, K, N, index=3000 + K + N, group=group)
+        want = orc.dequant(Wp, s, Zp, group).astype(np.float16)
+        _, dW, dS, dZ = binding.to_device(np.zeros((1, K), np.float16), Wp, s, Zp)
+        say("dequant", K, N, group)
+        W16 = torch.full((K, N), float("nan"), dtype=torch.float16, device="cuda")
+        binding.dequant(dW, dS, dZ, group, out=W16)
+        torch.cuda.synchronize()
+        got = W16.cpu().numpy()
+        assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), (K, N, group)
+
+
 # ------------------------------------------------------------ full configs ---
 
 def _sample_cols(N, count, seed):

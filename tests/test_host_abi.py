@@ -56,6 +56,11 @@ def test_argument_checks_need_no_gpu(binding):
     assert g(18, 16, 16, 16, 128, 1, 8, 128, 16, 0) == binding.ERR_ALIGN
     assert binding.raw_gemm_ws(16, 16, 16, 16, 128, 1, 8, 256, 16, 0, -1, 2, 0, 0) == binding.ERR_NULL
     assert binding.raw_gemm_ws(16, 16, 16, 16, 128, 1, 8, 256, 16, 0, -1, 2, 128, 1 << 20) == binding.ERR_ALIGN
+    dq = binding.lib().w4a16_dequant  # (Wpacked, scales, zeros, group, N, K, W16, stream)
+    assert dq(16, 16, 16, 128, 8, 128, 0, 0) == binding.ERR_NULL
+    assert dq(16, 16, 16, 128, 12, 128, 16, 0) == binding.ERR_SHAPE
+    assert dq(16, 16, 16, 48, 8, 96, 16, 0) == binding.ERR_GROUP
+    assert dq(16, 16, 16, 128, 8, 128, 24, 0) == binding.ERR_ALIGN
     with pytest.raises(binding.W4A16Error) as e:
         binding.query_plan(5, 64, 256, 128, kernel=binding.KERNEL_WAVE_SPLIT)  # that family is for M <= 4
     assert e.value.status == binding.ERR_UNSUPPORTED
