@@ -33,7 +33,7 @@ COLD_BYTES = 640 * 1024 * 1024
 # HBM bytes per launch of the headline kernel, from the committed rocprofv3 --pmc summaries
 # (profiles/hbm_traffic.json: FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size).
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-KERNEL_NAMES = {0: "wave_split_kernel", 1: "mfma_reg_kernel", 2: "mfma_rows_kernel", 3: "stripe_kernel", 4: "tile_kernel"}
+KERNEL_NAMES = {0: "wave_split_kernel", 3: "stripe_kernel", 4: "tile_kernel"}
 
 
 def measured_traffic(key):
@@ -143,7 +143,7 @@ def fig2(torch, binding, wl, max_steps):
             auto, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), host=h)
             dp = {}
             for fam, kid in (("wave_split", binding.KERNEL_WAVE_SPLIT), ("stripe", binding.KERNEL_STRIPE),
-                             ("tile", binding.KERNEL_TILE), ("mfma_rows", binding.KERNEL_MFMA_ROWS)):
+                             ("tile", binding.KERNEL_TILE)):
                 if (kid == binding.KERNEL_WAVE_SPLIT and M > 4) or (kid == binding.KERNEL_STRIPE and M > 16):
                     continue
                 if binding.query_plan(M, c.N, c.K, c.group, kid, 1)["split"] != 1:

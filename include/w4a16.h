@@ -72,9 +72,7 @@ typedef enum {
 typedef enum {
     W4A16_KERNEL_AUTO = -1,
     W4A16_KERNEL_WAVE_SPLIT = 0, /* M <= 4: narrow column tile per workgroup, its 16 waves split K, LDS reduction */
-    W4A16_KERNEL_MFMA_REG = 1,   /* any M: 256-column tiles, weights unpacked straight into MFMA operand registers */
-    W4A16_KERNEL_MFMA_ROWS = 2,  /* any M, meant for M > 16: as MFMA_REG with 32 or 64 rows of X staged in LDS per
-                                    workgroup, every unpacked weight word reused over the row tiles               */
+    /* 1 and 2 belonged to two earlier families, retired: W4A16_ERR_UNSUPPORTED */
     W4A16_KERNEL_STRIPE = 3,     /* M <= 16; the scheduler's choice for M <= 2 (M <= 4) from about 10 MB (48 MB) of
                                     packed weights on: 256-column stripe x K slice per workgroup, its waves own
                                     contiguous runs of the slice (LDS reduction); slices of different workgroups

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libw4a16.so")
 
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_GROUP, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORTED = range(1, 8)
-KERNEL_AUTO, KERNEL_WAVE_SPLIT, KERNEL_MFMA_REG, KERNEL_MFMA_ROWS, KERNEL_STRIPE, KERNEL_TILE = -1, 0, 1, 2, 3, 4
+KERNEL_AUTO, KERNEL_WAVE_SPLIT, KERNEL_STRIPE, KERNEL_TILE = -1, 0, 3, 4  # 1 and 2: retired families
 
 EXPORTS = (
     "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_workspace_bytes", "w4a16_query_plan",

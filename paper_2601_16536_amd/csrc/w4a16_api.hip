@@ -85,15 +85,10 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 //   S = compute units / workgroups, rounded down (a workgroup too many would run as a second round).
 //   Its time does not depend on M up to 16; STRIPE's grows with the S M N atomic adds of its finish.
 //
-// The families below are kept as forced plans (w4a16_gemm_ex) for comparison:
-// WAVE_SPLIT (M <= 4): one workgroup of sixteen waves per column tile of 32 or
-//   64 columns; the sixteen waves are sixteen K slices whose partial results
-//   meet in LDS.  A split across workgroups is added only when the column tiles
-//   cover at most a quarter of the compute units and the slices stay long.
-// MFMA_REG (M <= 16): 256-column tiles shared by four waves; S fills the GPU with
-//   about two workgroups per compute unit, bounded by the partial-sum traffic
-//   (8 S M N bytes written and read against K N / 2 bytes of weights).
-// MFMA_ROWS: the same tiles with 32 or 64 rows of X per workgroup.
+// WAVE_SPLIT (M <= 4) is kept as a forced plan (w4a16_gemm_ex), the data-parallel form for comparisons:
+//   one workgroup of sixteen waves per column tile of 32 or 64 columns; the sixteen waves are sixteen K
+//   slices whose partial results meet in LDS.  A split across workgroups is added only when the column
+//   tiles cover at most a quarter of the compute units and the slices stay long.
 //
 // How the K slices of different workgroups of a STRIPE or TILE plan meet: in the 64-bit fixed-point accumulator (one
 // returning atomic add per output and slice; measured: the GPU retires about 150 of them per nanosecond)
@@ -138,8 +133,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         const bool stripe = (M <= 2 && packed >= 10e6) || (M <= 4 && packed >= 48e6);
         kernel = stripe ? W4A16_KERNEL_STRIPE : W4A16_KERNEL_TILE;
     }
-    if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_MFMA_REG && kernel != W4A16_KERNEL_MFMA_ROWS &&
-        kernel != W4A16_KERNEL_STRIPE && kernel != W4A16_KERNEL_TILE)
+    if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_STRIPE && kernel != W4A16_KERNEL_TILE)
         return W4A16_ERR_UNSUPPORTED;
     if (kernel == W4A16_KERNEL_WAVE_SPLIT && M > 4) return W4A16_ERR_UNSUPPORTED;
     if (kernel == W4A16_KERNEL_STRIPE && M > 16) return W4A16_ERR_UNSUPPORTED;
@@ -213,7 +207,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->workspace_bytes = workspace_of(kernel, M, N, S);
         return W4A16_OK;
     }
-    if (kernel == W4A16_KERNEL_WAVE_SPLIT) {
+    {  // WAVE_SPLIT
         p->tile_n = (N + 63) / 64 >= cus ? 64 : 32;
         p->tile_m = 4;
         p->waves_k = 16;
@@ -229,21 +223,6 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
                 S = (int)(cus / tiles);
                 if (S > per_wg / (128 * 1024)) S = (int)(per_wg / (128 * 1024));
             }
-        }
-    } else {
-        p->tile_n = kTileN;
-        p->tile_m = kernel == W4A16_KERNEL_MFMA_REG ? 16 : (M <= 32 ? 32 : 64);
-        p->waves_k = 1;
-        p->threads = kThreads;
-        tiles = (long long)((N + kTileN - 1) / kTileN) * ((M + p->tile_m - 1) / p->tile_m);
-        if (S == 0) {
-            const long long target = 2LL * cus;  // two workgroups (eight waves) per compute unit
-            S = (int)((target + tiles / 2) / tiles);
-            // partial traffic (8 S M N bytes) at most ~1/8 of the weight bytes (K N / 2) for the
-            // bandwidth-bound small M; for M > 16, where the MFMA work needs every compute unit,
-            // at most the weight bytes themselves
-            const long long cap = M <= 16 ? (long long)K / (128LL * M) : (long long)K / (16LL * M);
-            if (S > cap) S = (int)cap;
         }
     }
     if (S < 1) S = 1;
@@ -363,9 +342,7 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
 
     hipError_t e = plan.kernel == W4A16_KERNEL_STRIPE       ? launch_stripe(a, finish, sync, plan.waves_k, st)
                    : plan.kernel == W4A16_KERNEL_TILE       ? launch_tile(a, finish, sync, plan.tile_m, plan.waves_k, st)
-                   : plan.kernel == W4A16_KERNEL_WAVE_SPLIT ? launch_wave_split(a, plan.tile_n, st)
-                   : plan.kernel == W4A16_KERNEL_MFMA_ROWS  ? launch_mfma_rows(a, plan.tile_m, st)
-                                                            : launch_mfma_reg(a, st);
+                                                            : launch_wave_split(a, plan.tile_n, st);
     if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
     if (finish == kFinishSecondPass) {
         e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);

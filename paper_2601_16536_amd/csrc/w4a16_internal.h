@@ -21,14 +21,9 @@ struct GemmArgs {
     int groups_per_split;
 };
 
-constexpr int kTileN = 256;         // columns per workgroup of the MFMA_REG family (4 waves x 64)
-constexpr int kThreads = 256;
-constexpr int kLdsBudget = 32768;   // bytes of LDS one workgroup stages X into
 
 // Multiply launchers: enqueue on `stream`, return the launch status.
-hipError_t launch_mfma_reg(const GemmArgs &a, hipStream_t stream);
 hipError_t launch_wave_split(const GemmArgs &a, int tile_n, hipStream_t stream);
-hipError_t launch_mfma_rows(const GemmArgs &a, int tile_m, hipStream_t stream);
 // How the K slices of different workgroups meet (the scheduler's choice per shape).
 enum Finish : int {
     kFinishDirect = 0,       // S = 1: the workgroup casts and stores Y

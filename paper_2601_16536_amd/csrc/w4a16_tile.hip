@@ -523,7 +523,7 @@ hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, 
     if (waves < 4 || waves > 8 || a.group % (8 * kBlockRows) != 0) return hipErrorInvalidValue;
     if (rows_x != 16 && rows_x != 32 && rows_x != 64) return hipErrorInvalidValue;
     if (!finish_args_ok(a, finish, sync)) return hipErrorInvalidValue;
-    const bool by_group = a.group == 128;
+    const bool by_group = a.group == 128;  // else the loop over single blocks (measured: 0.5-0.7 us slower on small shapes, equal on large)
     Launch l;
     if (!prepare(a, rows_x, waves, by_group, &l)) return hipErrorInvalidValue;
     if (by_group) {

@@ -77,7 +77,7 @@ def test_small_shapes_every_split(gpu, M, K, N, group):
     X, Wp, s, Zp = wl.make(M, K, N, index=1000 + M + K + N, group=group)
     ref = orc.gemm(X, Wp, s, Zp, group)
     G = K // group
-    kernels = [binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS, binding.KERNEL_TILE] + (
+    kernels = [binding.KERNEL_AUTO, binding.KERNEL_TILE] + (
         [binding.KERNEL_WAVE_SPLIT] if M <= 4 else []) + ([binding.KERNEL_STRIPE] if M <= 16 else [])
     for kernel in kernels:
         for split in sorted({0, 1, 2, 3, G}):
@@ -148,7 +148,7 @@ def test_integer_case_bit_exact_with_zero_points_and_splits(gpu):
     Wp, Zp = wl.pack_along_k(q), wl.pack_along_n(z)
     ref = orc.gemm(X, Wp, s, Zp, group)
     assert np.abs(ref).max() < 2048 and np.array_equal(ref, np.round(ref))
-    for kernel in (0, 1, 3, 4):
+    for kernel in (0, 3, 4):
         for split in (1, 2, 4):
             say("integer exact zp", kernel, split)
             Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=kernel, split=split)
@@ -211,8 +211,7 @@ def test_symmetric_int4_as_zero_point_eight(gpu):
 
 def binding_kernels(gpu):
     _, binding = gpu
-    return (binding.KERNEL_AUTO, binding.KERNEL_WAVE_SPLIT, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS,
-            binding.KERNEL_STRIPE, binding.KERNEL_TILE)
+    return (binding.KERNEL_AUTO, binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE, binding.KERNEL_TILE)
 
 
 def test_deterministic_and_split_invariant(gpu):

@@ -70,6 +70,9 @@ def test_argument_checks_need_no_gpu(binding):
         binding.query_plan(17, 64, 256, 128, kernel=binding.KERNEL_STRIPE)  # that family is for M <= 16
     with pytest.raises(binding.W4A16Error):
         binding.query_plan(1, 64, 256, 128, kernel=5)
+    for retired in (1, 2):  # ids of two earlier kernel families
+        with pytest.raises(binding.W4A16Error):
+            binding.query_plan(1, 64, 256, 128, kernel=retired)
 
 
 SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336), (16, 4096, 14336), (1, 8192, 28672),
@@ -80,7 +83,7 @@ SHAPES = [(1, 1024, 4096), (1, 4096, 11008), (1, 4096, 14336), (4, 4096, 14336),
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_plans_are_well_formed(binding, M, N, K):
     G = K // 128
-    for kernel in (binding.KERNEL_AUTO, binding.KERNEL_MFMA_REG, binding.KERNEL_MFMA_ROWS, binding.KERNEL_TILE) + (
+    for kernel in (binding.KERNEL_AUTO, binding.KERNEL_TILE) + (
             (binding.KERNEL_WAVE_SPLIT,) if M <= 4 else ()) + ((binding.KERNEL_STRIPE,) if M <= 16 else ()):
         for split in sorted({0, 1, 2, 7, G}):
             if split > G:
@@ -109,7 +112,7 @@ def test_plans_are_well_formed(binding, M, N, K):
             elif p["kernel"] == binding.KERNEL_TILE:
                 assert p["threads"] == 512 and p["waves_k"] == 8 and p["tile_n"] == 64 and p["tile_m"] in (16, 32, 64)
             else:
-                assert p["threads"] in (256, 1024) and p["waves_k"] in (1, 16)
+                assert p["threads"] == 1024 and p["waves_k"] == 16
     assert binding.workspace_bytes(M, N, K, 128) >= binding.query_plan(M, N, K, 128)["workspace_bytes"]
 
 
