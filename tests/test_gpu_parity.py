@@ -258,6 +258,60 @@ def test_non_default_stream_and_caller_workspace(gpu):
     assert e.value.status == binding.ERR_WORKSPACE
 
 
+def test_hip_graph_replays_match_eager(gpu):
+    """What bench.py times: GEMMs recorded into a HIP graph and replayed.  Every kind of finish is recorded
+    (direct store, accumulator in the library's and in a caller's workspace - the latter with its clearing
+    kernel -, FP32 partials with the second pass); the graph is replayed several times with eager work and
+    synchronisations in between, and every replay must reproduce the eager results bit for bit."""
+    torch, binding = gpu
+    cases = [  # M, K, N, kernel, split
+        (1, 4096, 1024, binding.KERNEL_STRIPE, 0),   # accumulator (library-owned)
+        (8, 2048, 512, binding.KERNEL_TILE, 4),      # accumulator
+        (3, 1024, 264, binding.KERNEL_TILE, 1),      # direct
+        (130, 768, 2056, binding.KERNEL_TILE, 3),    # S M N > 640 K adds: FP32 partials + second pass
+        (2, 2048, 520, binding.KERNEL_WAVE_SPLIT, 2),
+    ]
+    dev, eager, outs = [], [], []
+    for (M, K, N, kernel, split) in cases:
+        X, Wp, s, Zp = wl.make(M, K, N, index=4000 + M + K + N)
+        d = binding.to_device(X, Wp, s, Zp)
+        dev.append(d)
+        ref = orc.gemm(X, Wp, s, Zp, 128)
+        say("graph: eager", (M, K, N), kernel, split, binding.query_plan(M, N, K, 128, kernel, split))
+        Y = binding.gemm_ex(*d, 128, kernel=kernel, split=split)  # also lets the library allocate what the plan needs
+        torch.cuda.synchronize()
+        assert err_ratio(Y.cpu().numpy(), ref) <= 1.0
+        eager.append(Y.clone())
+        outs.append(torch.empty_like(Y))
+    # a caller's workspace for the second case, poisoned: its clearing kernel is part of the graph
+    M, K, N, kernel, split = cases[1]
+    plan = binding.query_plan(M, N, K, 128, kernel, split)
+    assert plan["workspace_bytes"] == M * N * 8
+    ws = torch.full((plan["workspace_bytes"],), 0xFF, dtype=torch.uint8, device="cuda")
+    out_ws = torch.empty_like(eager[1])
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    say("graph: capture")
+    with torch.cuda.graph(g):
+        for d, (M, K, N, kernel, split), Y in zip(dev, cases, outs):
+            binding.gemm_ex(*d, 128, kernel=kernel, split=split, out=Y, stream=torch.cuda.current_stream())
+        binding.gemm_ws(*dev[1], 128, ws, kernel=cases[1][3], split=cases[1][4], out=out_ws, stream=torch.cuda.current_stream())
+    for rep in range(4):
+        for Y in outs + [out_ws]:
+            Y.fill_(float("nan"))
+        ws.fill_(0xFF if rep % 2 else 0x5A)
+        # eager work between the replays, on the same library state
+        Ye = binding.gemm_ex(*dev[0], 128, kernel=cases[0][3], split=cases[0][4])
+        torch.cuda.synchronize()
+        assert torch.equal(Ye, eager[0])
+        say("graph: replay", rep)
+        g.replay()
+        torch.cuda.synchronize()
+        for Y, E in zip(outs, eager):
+            assert torch.equal(Y, E), rep
+        assert torch.equal(out_ws, eager[1]), rep
+
+
 def test_stripe_accumulator_is_left_clean(gpu):
     """The STRIPE family adds the K slices of different workgroups into a 64-bit fixed-point accumulator
     (one atomic add each) that the last arriver clears: calls of different shapes and splits in a row, on the
