@@ -157,6 +157,22 @@ def fig2(torch, binding, wl, max_steps):
             log(json.dumps(row))
             rows.append(row)
         del h
+    # K << N: the scheduler's plan against forced splits of the same family
+    for name, c in wl.WIDE.items():
+        h = wl.make_config(name)
+        steps = max(50, min(max_steps, int(2e5 / max(1.0, 1e-6 * c.K * c.N / 16))))
+        for M in c.Ms:
+            auto, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), host=h)
+            forced = {}
+            for S in (1, 2, 4):
+                r, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), kernel=auto["plan"]["kernel"],
+                                    split=S, host=h)
+                forced["S=%d" % S] = r["us_per_gemm"]
+            row = {"shape": name, "N": c.N, "K": c.K, "M": M, "split_k_us": auto["us_per_gemm"], "split_k_plan": auto["plan"],
+                   "forced_us": forced}
+            log(json.dumps(row))
+            rows.append(row)
+        del h
     return rows
 
 

@@ -78,7 +78,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // scheduler (kernel = AUTO, split = 0) chooses them from the shape alone:
 //
 // STRIPE (M <= 2 from about 10 MB of packed weights on, M <= 4 from about 48 MB on): 256-column stripes
-//   x S slices of K with S = compute units / stripes, so that one workgroup runs per compute unit; ten
+//   x S slices of K with S = compute units / stripes, rounded down: one workgroup per compute unit; ten
 //   to sixteen waves of a workgroup own contiguous runs of the slice's rows.
 // TILE (everything else): 64-column tiles x 16, 32 or 64 rows of X per workgroup (as many rows as still
 //   leave a workgroup per compute unit at S = 1), eight waves own contiguous runs of the slice's K;
@@ -146,7 +146,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->tile_m = M <= 4 ? 4 : 16;
         tiles = (N + 255) / 256;
         const int wmin = stripe_min_waves(M), wmax = stripe_max_waves(M);
-        if (S == 0) S = (int)((cus + tiles / 2) / tiles);  // one workgroup per compute unit
+        if (S == 0) S = (int)(cus / tiles);  // at most one workgroup per compute unit (measured, N = 14336: 280 workgroups 11.4 us, 224 8.9 us)
         if (S < 1) S = 1;
         if (S > G) S = G;
         int gps = (G + S - 1) / S;

@@ -61,8 +61,20 @@ FIG2 = {
 }
 
 
+# The opposite regime, K << N (up-projections of the same layers): Section 4.1 expects Split-K to gain only
+# "when K >> N", so here it should not be chosen, and forcing it should lose.
+WIDE = {
+    "w1": Config("w1", 31, 4096, 11008, (1, 16)),
+    "w2": Config("w2", 32, 4096, 14336, (1, 16)),
+    "w3": Config("w3", 33, 8192, 28672, (1, 16)),
+}
+
+
 def config(name: str) -> Config:
-    return CONFIGS[name] if name in CONFIGS else FIG2[name]
+    for table in (CONFIGS, FIG2, WIDE):
+        if name in table:
+            return table[name]
+    raise KeyError(name)
 
 
 def pack_along_k(q: np.ndarray) -> np.ndarray:
