@@ -298,14 +298,20 @@ def main():
                                                                           cfg.group, res["cache"]),
                    "plan": res["plan"]},
         "achieved_TBps": res["GBps"] * 1e-3, "achieved_TFLOPs": res["TFLOPs"],
-        "roofline": {"bound": "hbm", "achieved": res["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": res["hbm_frac"], "traffic": measured_traffic("%s_M%d" % (args.config, args.M)),
+        # the roofline that bounds the kernel: HBM below the ridge of 2.5 PFLOP/s over 8 TB/s = 312.5 flop/byte, MFMA above
+        "roofline": ({"bound": "hbm", "achieved": res["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["hbm_frac"]}
+                     if 2.0 * args.M * cfg.K * cfg.N / res["algorithmic_bytes"] < 1e3 * MFMA_FP16_PEAK_TFLOPS / HBM_PEAK_GBS else
+                     {"bound": "mfma", "achieved": res["TFLOPs"], "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": res["mfma_frac"]}),
+    }
+    line["roofline"].update({"traffic": measured_traffic("%s_M%d" % (args.config, args.M)),
                      "launches_per_step": 1 if res["plan"]["split"] == 1 or res["plan"]["workspace_bytes"] ==
                      8 * args.M * cfg.N else 2,
-                     "kernel": KERNEL_NAMES.get(res["plan"]["kernel"], "?"),
-                     "algorithmic_bytes_per_launch": res["algorithmic_bytes"]},
-        "cpu_baseline": cpu,
-    }
+                     "kernel": ("tile_group_kernel" if res["plan"]["kernel"] == 4 and cfg.group == 128 else
+                                KERNEL_NAMES.get(res["plan"]["kernel"], "?")),
+                     "algorithmic_bytes_per_launch": res["algorithmic_bytes"],
+                     "algorithmic_flops_per_launch": 2.0 * args.M * cfg.K * cfg.N})
+    line["cpu_baseline"] = cpu
 
     if args.table:
         rows = []
