@@ -339,6 +339,7 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
     a.group = group; a.M = M; a.N = N; a.K = K;
     a.split = plan.split;
     a.groups_per_split = plan.groups_per_split;
+    a.groups = K / group;
 
     hipError_t e = plan.kernel == W4A16_KERNEL_STRIPE       ? launch_stripe(a, finish, sync, plan.waves_k, st)
                    : plan.kernel == W4A16_KERNEL_TILE       ? launch_tile(a, finish, sync, plan.tile_m, plan.waves_k, st)

@@ -19,6 +19,7 @@ struct GemmArgs {
     int group, M, N, K;
     int split;                // S
     int groups_per_split;
+    int groups;               // K / group (kept here so that no kernel divides for it)
 };
 
 

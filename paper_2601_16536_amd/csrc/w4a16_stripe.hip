@@ -91,22 +91,25 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int waves = blockDim.x >> 6;
-    const int nstripes = (a.N + kStripe - 1) / kStripe;
-    const int stripe = blockIdx.x % nstripes, slice = blockIdx.x / nstripes;
+    // grid: x = stripe, y = K slice.  Integer divisions cost dozens of dependent scalar instructions each,
+    // all of them ahead of the first load, so the index arithmetic below avoids them.
+    const int stripe = blockIdx.x, slice = blockIdx.y;
     const int col0 = stripe * kStripe + 4 * lane;
     const bool ok = col0 < a.N;
 
     // the workgroup's K slice: groups, packed rows, blocks; this wave's run of blocks
     const int gbeg = slice * a.groups_per_split;
     int gend = gbeg + a.groups_per_split;
-    if (gend > a.K / a.group) gend = a.K / a.group;
+    if (gend > a.groups) gend = a.groups;
     const int groups = gend - gbeg;
     const int rows = groups * (a.group / 8);
     const int row_base = gbeg * (a.group / 8);
     const uint32_t nblocks = (uint32_t)rows / kBlockRows;
     const uint32_t bpg = (uint32_t)a.group / (8 * kBlockRows);  // blocks per group
-    const uint32_t wb0 = (uint32_t)((unsigned long long)nblocks * wave / waves);
-    const uint32_t wb1 = (uint32_t)((unsigned long long)nblocks * (wave + 1) / waves);
+    // runs of nblocks / waves blocks, the first nblocks % waves of them one block longer
+    const uint32_t per = nblocks / (uint32_t)waves, extra = nblocks - per * (uint32_t)waves;
+    const uint32_t wb0 = per * (uint32_t)wave + ((uint32_t)wave < extra ? (uint32_t)wave : extra);
+    const uint32_t wb1 = wb0 + per + ((uint32_t)wave < extra ? 1u : 0u);
 
     const uint32_t row_w = (uint32_t)a.N * 4u, row_s = (uint32_t)a.N * 2u, row_z = (uint32_t)(a.N >> 3) * 4u;
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
@@ -308,7 +311,8 @@ hipError_t launch_m(const GemmArgs &a, int finish, unsigned long long *sync, int
                                            hipFuncAttributeMaxDynamicSharedMemorySize, stripe_lds_limit());
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((stripe_kernel<MROWS>), dim3(nstripes * a.split), dim3(waves * 64), lds, stream, a, finish, sync, red_waves);
+    if (a.split > 65535) return hipErrorInvalidValue;  // slices are the grid's y
+    hipLaunchKernelGGL((stripe_kernel<MROWS>), dim3(nstripes, a.split), dim3(waves * 64), lds, stream, a, finish, sync, red_waves);
     return hipGetLastError();
 }
 

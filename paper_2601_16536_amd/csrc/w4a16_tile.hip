@@ -65,10 +65,20 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int f
     // workgroup -> (column tile, K slice, row block): the row blocks of one (tile, slice) are neighbours on one XCD
     const int ntiles = (a.N + kTileCols - 1) / kTileCols;
     const int units = ntiles * a.split;
-    const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
-    const int rb = local % row_blocks, unit = (local / row_blocks) * kXcds + xcd;
+    // (integer divisions cost dozens of dependent scalar instructions each, all ahead of the first load:
+    // the common cases take none)
+    int rb = 0, unit = (int)blockIdx.x;
+    if (row_blocks > 1) {
+        const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+        rb = local % row_blocks;
+        unit = (local / row_blocks) * kXcds + xcd;
+    }
     if (unit >= units) return;  // the grid is rounded up to whole XCD rounds
-    const int tile = unit % ntiles, slice = unit / ntiles;
+    int tile = unit, slice = 0;
+    if (a.split > 1) {
+        slice = unit / ntiles;
+        tile = unit - slice * ntiles;
+    }
     const int m0 = rb * Sh::kRowsX;
     const int col0 = tile * kTileCols + 4 * j;
     const bool ok = col0 < a.N;
@@ -76,14 +86,16 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int f
     // the workgroup's K slice: groups, packed rows, blocks; this wave's run of blocks
     const int gbeg = slice * a.groups_per_split;
     int gend = gbeg + a.groups_per_split;
-    if (gend > a.K / a.group) gend = a.K / a.group;
+    if (gend > a.groups) gend = a.groups;
     const int groups = gend - gbeg;
     const int rows = groups * (a.group / 8);
     const int row_base = gbeg * (a.group / 8);
     const uint32_t nblocks = (uint32_t)rows / kBlockRows;
     const uint32_t bpg = (uint32_t)a.group / (8 * kBlockRows);  // blocks per group
-    const uint32_t wb0 = (uint32_t)((unsigned long long)nblocks * wave / waves);
-    const uint32_t wb1 = (uint32_t)((unsigned long long)nblocks * (wave + 1) / waves);
+    // runs of nblocks / waves blocks, the first nblocks % waves of them one block longer
+    const uint32_t per = nblocks / (uint32_t)waves, extra = nblocks - per * (uint32_t)waves;
+    const uint32_t wb0 = per * (uint32_t)wave + ((uint32_t)wave < extra ? (uint32_t)wave : extra);
+    const uint32_t wb1 = wb0 + per + ((uint32_t)wave < extra ? 1u : 0u);
 
     const uint32_t row_w = (uint32_t)a.N * 4u, row_s = (uint32_t)a.N * 2u, row_z = (uint32_t)(a.N >> 3) * 4u;
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
@@ -286,10 +298,20 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
 
     const int ntiles = (a.N + kTileCols - 1) / kTileCols;
     const int units = ntiles * a.split;
-    const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
-    const int rb = local % row_blocks, unit = (local / row_blocks) * kXcds + xcd;
+    // (integer divisions cost dozens of dependent scalar instructions each, all ahead of the first load:
+    // the common cases take none)
+    int rb = 0, unit = (int)blockIdx.x;
+    if (row_blocks > 1) {
+        const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+        rb = local % row_blocks;
+        unit = (local / row_blocks) * kXcds + xcd;
+    }
     if (unit >= units) return;  // the grid is rounded up to whole XCD rounds
-    const int tile = unit % ntiles, slice = unit / ntiles;
+    int tile = unit, slice = 0;
+    if (a.split > 1) {
+        slice = unit / ntiles;
+        tile = unit - slice * ntiles;
+    }
     const int m0 = rb * Sh::kRowsX;
     const int col0 = tile * kTileCols + 4 * j;
     const bool ok = col0 < a.N;
@@ -297,11 +319,12 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
     // the slice's groups, and this wave's run of them
     const int gbeg = slice * a.groups_per_split;
     int gend = gbeg + a.groups_per_split;
-    if (gend > a.K / a.group) gend = a.K / a.group;
+    if (gend > a.groups) gend = a.groups;
     const int groups = gend - gbeg;
-    const int g0 = gbeg + (int)((long long)groups * wave / waves);
-    const int g1 = gbeg + (int)((long long)groups * (wave + 1) / waves);
-    const int ng = g1 - g0;
+    // runs of groups / waves groups, the first groups % waves of them one group longer
+    const int per = (int)((uint32_t)groups / (uint32_t)waves), extra = groups - per * waves;
+    const int g0 = gbeg + per * wave + (wave < extra ? wave : extra);
+    const int ng = per + (wave < extra ? 1 : 0);
 
     const uint32_t row_w = (uint32_t)a.N * 4u, row_s = (uint32_t)a.N * 2u, row_z = (uint32_t)(a.N >> 3) * 4u;
     const uint32_t step_w = kBlockRows * row_w;  // one block further
