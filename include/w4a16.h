@@ -143,6 +143,15 @@ int w4a16_reduce(const float *partials, int S, int M, int N, void *Y, void *stre
 int w4a16_dequant(const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int N, int K,
                   void *W16, void *stream);
 
+/* Offline tool (Section 2.1, Eq. 1: x_q = round(x / s) + z): quantizes FP16 weights W16 [K, N] (row-major, device
+ * pointer) into the three tensors w4a16_gemm reads, all owned by the caller and fully overwritten: Wpacked [K/8, N],
+ * scales FP16 [K/group, N], zeros [K/group, N/8].  The paper leaves the choice of s and z open; per group of one
+ * column, in FP32: lo = min(min w, 0), hi = max(max w, 0), s = fp16((hi - lo) / 15) (1 if that is 0),
+ * z = clamp(rint(-lo / s), 0, 15), q = clamp(rint(w / s) + z, 0, 15), rounding to nearest even.  Inputs must be
+ * finite.  Same shape rules and error codes as w4a16_gemm. */
+int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, void *scales, uint32_t *zeros,
+                   void *stream);
+
 /* Text for a status code (static storage). */
 const char *w4a16_status_string(int status);
 

@@ -17,7 +17,7 @@ KERNEL_AUTO, KERNEL_WAVE_SPLIT, KERNEL_STRIPE, KERNEL_TILE = -1, 0, 3, 4  # 1 an
 
 EXPORTS = (
     "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_workspace_bytes", "w4a16_query_plan",
-    "w4a16_reduce", "w4a16_dequant", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
+    "w4a16_reduce", "w4a16_dequant", "w4a16_quantize", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
 )
 
 
@@ -68,6 +68,7 @@ def lib():
         L.w4a16_query_plan.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(Plan)]
         L.w4a16_reduce.argtypes = [vp, ci, ci, ci, vp, vp]
         L.w4a16_dequant.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp]
+        L.w4a16_quantize.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
         L.w4a16_status_string.argtypes = [ci]
         L.w4a16_status_string.restype = ctypes.c_char_p
         L.w4a16_last_hip_error.argtypes = []
@@ -204,6 +205,25 @@ def dequant(Wpacked, scales, zeros, group: int, out=None, stream=None):
     if rc:
         raise W4A16Error(rc, "w4a16_dequant")
     return W16
+
+
+def quantize(W16, group: int, stream=None):
+    """Offline tool (Eq. 1): FP16 weights [K, N] on the GPU -> (Wpacked int32 [K/8, N], scales float16 [G, N],
+    zeros int32 [G, N/8]) in the layout gemm reads."""
+    import torch
+    if not W16.is_cuda or W16.dtype != torch.float16 or not W16.is_contiguous() or W16.dim() != 2:
+        raise TypeError("W16 must be a contiguous CUDA float16 matrix [K, N]")
+    K, N = W16.shape
+    if group < 1 or K % group or K % 8 or N % 8:
+        raise W4A16Error(2, "binding.quantize (shape)")
+    G = K // group
+    Wp = torch.empty((K // 8, N), dtype=torch.int32, device=W16.device)
+    s = torch.empty((G, N), dtype=torch.float16, device=W16.device)
+    Zp = torch.empty((G, N // 8), dtype=torch.int32, device=W16.device)
+    rc = lib().w4a16_quantize(W16.data_ptr(), group, N, K, Wp.data_ptr(), s.data_ptr(), Zp.data_ptr(), _stream(stream))
+    if rc:
+        raise W4A16Error(rc, "w4a16_quantize")
+    return Wp, s, Zp
 
 
 def shutdown() -> None:

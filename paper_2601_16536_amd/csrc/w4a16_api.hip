@@ -415,6 +415,20 @@ int w4a16_dequant(const uint32_t *Wpacked, const void *scales, const uint32_t *z
     return W4A16_OK;
 }
 
+int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, void *scales, uint32_t *zeros,
+                   void *stream)
+{
+    t_hip_error[0] = 0;
+    if (!W16 || !Wpacked || !scales || !zeros) return W4A16_ERR_NULL;
+    int rc = check_shape(group, 1, N, K);
+    if (rc) return rc;
+    if (!aligned16(W16) || !aligned16(Wpacked) || !aligned16(scales) || !aligned16(zeros)) return W4A16_ERR_ALIGN;
+    hipError_t e = launch_quantize(static_cast<const uint16_t *>(W16), group, N, K, Wpacked, static_cast<uint16_t *>(scales),
+                                   zeros, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+    return W4A16_OK;
+}
+
 const char *w4a16_status_string(int status)
 {
     switch (status) {

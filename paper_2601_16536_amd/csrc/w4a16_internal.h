@@ -60,6 +60,9 @@ hipError_t launch_accumulator_clear(unsigned long long *acc, size_t n, hipStream
 // Phase 1 alone (Algorithm 1): W16[K, N] = fp16(s (q - z)) in global memory, for the unfused variant.
 hipError_t launch_dequant(const uint32_t *Wp, const uint16_t *scales, const uint32_t *Zp, int group, int N, int K,
                           uint16_t *W16, hipStream_t stream);
+// Offline quantizer (Eq. 1): FP16 weights [K, N] -> packed codes, FP16 scales, packed zero points.
+hipError_t launch_quantize(const uint16_t *W16, int group, int N, int K, uint32_t *Wp, uint16_t *scales, uint32_t *Zp,
+                           hipStream_t stream);
 // Second pass (Algorithm 1, Phase 3).
 hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream);
 

@@ -61,6 +61,11 @@ def test_argument_checks_need_no_gpu(binding):
     assert dq(16, 16, 16, 128, 12, 128, 16, 0) == binding.ERR_SHAPE
     assert dq(16, 16, 16, 48, 8, 96, 16, 0) == binding.ERR_GROUP
     assert dq(16, 16, 16, 128, 8, 128, 24, 0) == binding.ERR_ALIGN
+    qz = binding.lib().w4a16_quantize  # (W16, group, N, K, Wpacked, scales, zeros, stream)
+    assert qz(16, 128, 8, 128, 16, 0, 16, 0) == binding.ERR_NULL
+    assert qz(16, 128, 8, 100, 16, 16, 16, 0) == binding.ERR_SHAPE
+    assert qz(16, 48, 8, 96, 16, 16, 16, 0) == binding.ERR_GROUP
+    assert qz(16, 128, 8, 128, 16, 16, 20, 0) == binding.ERR_ALIGN
     with pytest.raises(binding.W4A16Error) as e:
         binding.query_plan(5, 64, 256, 128, kernel=binding.KERNEL_WAVE_SPLIT)  # that family is for M <= 4
     assert e.value.status == binding.ERR_UNSUPPORTED
