@@ -156,6 +156,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
             gps = (gps + 1) / 2;
         S = (G + gps - 1) / gps;
         if (stripe_lds_bytes(M, group, gps, wmin) > (size_t)stripe_lds_limit()) return W4A16_ERR_UNSUPPORTED;
+        if (S > 65535) return W4A16_ERR_UNSUPPORTED;  // the slices are the grid's second dimension
         // waves: each should own at least four blocks of 16 k; twelve measured best on the large shapes for
         // M <= 4 (ten to sixteen are within 3 % of each other); the many-row form holds eight at most
         const long long nblocks = (long long)gps * (group / 16);
