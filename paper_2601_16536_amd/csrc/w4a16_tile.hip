@@ -276,7 +276,8 @@ struct GroupShape {
     static constexpr int kChunkBlocks = RT == 4 ? 1 : 4;         // blocks per staged chunk of X
     static constexpr int kChunks = 4 / kChunkBlocks;             // chunks per group
     static constexpr int kRingGroups = RT == 4 ? 1 : 2;          // groups of weights in flight per wave (registers)
-    static constexpr int kRowStride = kRowsX + 4;                // LDS entries per packed row (padded)
+    // LDS entries per packed row, padded: odd where sixteen lanes write sixteen packed rows of one row of X
+    static constexpr int kRowStride = kChunkBlocks == 4 ? kRowsX + 1 : kRowsX + 4;
     static constexpr int kPerLane = kChunkBlocks * kBlockRows * kRowsX / 64;
     static constexpr int kBufBytes = kChunkBlocks * kBlockRows * kRowStride * 16;
     static constexpr int kWaveBytes = 2 * kBufBytes;
@@ -347,30 +348,35 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
     };
 
     // ---- X: this wave's LDS (two chunk buffers), chunk loader and chunk writer ----
-    // Entry e = lane + 64 q of a chunk: packed row e & 3 of block (e >> 2) / rows of row (e >> 2) % rows of X,
-    // so four neighbouring lanes fetch 64 contiguous bytes.  For every q the row is (lane >> 2) + 16 (q % RT)
-    // and the block is q / RT: per lane one global offset per q % RT and one LDS slot, the rest are constants.
+    // Whole-group chunks (16 or 32 rows of X per workgroup): sixteen neighbouring lanes fetch the 256 contiguous
+    // bytes the group takes of one row of X, so that every cache line is used up by the instruction that brings
+    // it (64-byte pieces, one block per instruction, cost twice the L2 traffic: the other half of each line was
+    // gone from the L1 by the time the next block asked for it).  Load q of a lane: row 4 q + lane / 16, packed
+    // row lane % 16 of the group.  One-block chunks (64 rows): four neighbouring lanes fetch the 64 bytes of the
+    // block, load q: row lane / 4 + 16 q.
     unsigned char *wl = smem + (size_t)wave * Sh::kWaveBytes;
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(a.X), 0, (uint32_t)((size_t)a.M * a.K * 2), kRawBuffer);
-    uint32_t xg[RT];
+    constexpr bool kWholeGroup = Sh::kChunkBlocks == 4;
+    uint32_t xg[Sh::kPerLane];
 #pragma unroll
-    for (int s = 0; s < RT; ++s) {
-        const uint32_t m = (uint32_t)m0 + (uint32_t)(lane >> 2) + 16u * s;
-        xg[s] = m < (uint32_t)a.M ? (m * (uint32_t)a.K + ((uint32_t)g0 * 16u + (uint32_t)(lane & 3)) * 8u) * 2u : kOutOfRange;
+    for (int q = 0; q < Sh::kPerLane; ++q) {
+        const uint32_t m = (uint32_t)m0 + (kWholeGroup ? 4u * q + (uint32_t)(lane >> 4) : 16u * q + (uint32_t)(lane >> 2));
+        const uint32_t prow = (uint32_t)g0 * 16u + (uint32_t)(kWholeGroup ? lane & 15 : lane & 3);
+        xg[q] = m < (uint32_t)a.M ? (m * (uint32_t)a.K + prow * 8u) * 2u : kOutOfRange;
     }
-    const uint32_t xl0 = (uint32_t)(((lane & 3) * Sh::kRowStride + (lane >> 2)) * 16);
+    const uint32_t xl0 = kWholeGroup ? (uint32_t)(((lane & 15) * Sh::kRowStride + (lane >> 4)) * 16)
+                                     : (uint32_t)(((lane & 3) * Sh::kRowStride + (lane >> 2)) * 16);
     uint4_t xd[Sh::kPerLane];
     auto x_load = [&](uint32_t chunk) {  // chunk of the wave's run
         const uint32_t so = chunk * (Sh::kChunkBlocks * kBlockRows * 16u);
 #pragma unroll
-        for (int q = 0; q < Sh::kPerLane; ++q)
-            xd[q] = __builtin_amdgcn_raw_buffer_load_b128(rx, xg[q % RT], so + (q / RT) * (kBlockRows * 16u), 0);
+        for (int q = 0; q < Sh::kPerLane; ++q) xd[q] = __builtin_amdgcn_raw_buffer_load_b128(rx, xg[q], so, 0);
     };
     auto x_store = [&](int par) {
 #pragma unroll
         for (int q = 0; q < Sh::kPerLane; ++q)
-            *reinterpret_cast<uint4_t *>(wl + par * Sh::kBufBytes + xl0 + ((q / RT) * kBlockRows * Sh::kRowStride + 16 * (q % RT)) * 16) = permute_x(xd[q]);
+            *reinterpret_cast<uint4_t *>(wl + par * Sh::kBufBytes + xl0 + (kWholeGroup ? 4 * q : 16 * q) * 16) = permute_x(xd[q]);
     };
 
     float4_t tot[RT][4];
@@ -493,10 +499,13 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
 }
 
 // The waves' chunk buffers; the final sums reuse the space, a whole number of waves' tiles per round.
-size_t lds_bytes(int rows_x, int waves, bool by_group)
+enum Loop { kLoopBlocks = 0, kLoopGroups = 1 };  // which kernel: any group size; group = 128
+
+size_t lds_bytes(int rows_x, int waves, int loop)
 {
-    const size_t wave_bytes = by_group ? (rows_x == 16 ? GroupShape<1>::kWaveBytes : rows_x == 32 ? GroupShape<2>::kWaveBytes : GroupShape<4>::kWaveBytes)
-                                       : (rows_x == 16 ? Shape<1>::kWaveBytes : rows_x == 32 ? Shape<2>::kWaveBytes : Shape<4>::kWaveBytes);
+    const int rt = rows_x / 16;
+    const size_t wave_bytes = loop == kLoopGroups ? (rt == 1 ? GroupShape<1>::kWaveBytes : rt == 2 ? GroupShape<2>::kWaveBytes : GroupShape<4>::kWaveBytes)
+                                                  : (rt == 1 ? Shape<1>::kWaveBytes : rt == 2 ? Shape<2>::kWaveBytes : Shape<4>::kWaveBytes);
     const size_t stage = (size_t)waves * wave_bytes;
     const size_t one = (size_t)rows_x * kTileCols * 4;
     size_t red = one * waves;
@@ -510,9 +519,9 @@ struct Launch {
 };
 
 // Grid and LDS of a launch; false if the shape is beyond the kernels' 32-bit offsets.
-bool prepare(const GemmArgs &a, int rows_x, int waves, bool by_group, Launch *l)
+bool prepare(const GemmArgs &a, int rows_x, int waves, int loop, Launch *l)
 {
-    l->lds = lds_bytes(rows_x, waves, by_group);
+    l->lds = lds_bytes(rows_x, waves, loop);
     l->red_waves = (int)(l->lds / ((size_t)rows_x * kTileCols * 4));
     if (l->red_waves < 1) return false;
     if (l->red_waves > waves) l->red_waves = waves;
@@ -546,10 +555,10 @@ hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, 
     if (waves < 4 || waves > 8 || a.group % (8 * kBlockRows) != 0) return hipErrorInvalidValue;
     if (rows_x != 16 && rows_x != 32 && rows_x != 64) return hipErrorInvalidValue;
     if (!finish_args_ok(a, finish, sync)) return hipErrorInvalidValue;
-    const bool by_group = a.group == 128;  // else the loop over single blocks (measured: 0.5-0.7 us slower on small shapes, equal on large)
+    const int loop = a.group == 128 ? kLoopGroups : kLoopBlocks;  // the loop over single blocks: 0.5-0.7 us slower on small shapes, equal on large
     Launch l;
-    if (!prepare(a, rows_x, waves, by_group, &l)) return hipErrorInvalidValue;
-    if (by_group) {
+    if (!prepare(a, rows_x, waves, loop, &l)) return hipErrorInvalidValue;
+    if (loop == kLoopGroups) {
         if (rows_x == 16) return launch_kernel(&tile_group_kernel<1>, l, a, finish, sync, waves, stream);
         if (rows_x == 32) return launch_kernel(&tile_group_kernel<2>, l, a, finish, sync, waves, stream);
         return launch_kernel(&tile_group_kernel<4>, l, a, finish, sync, waves, stream);
