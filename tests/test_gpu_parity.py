@@ -113,6 +113,28 @@ def test_tile_family_every_row_block(gpu, rows_x, monkeypatch):
             assert r <= 1.0, (rows_x, M, K, N, group, split, r)
 
 
+def test_seeded_random_shapes(gpu):
+    """Forty-eight shapes drawn with a fixed seed (M 1..200, ragged N, K of 1..40 groups, group 32..256): the
+    scheduler's plan and one forced (family, split) each, all outputs against the oracle."""
+    _, binding = gpu
+    rng = np.random.default_rng(20260116)
+    for case in range(48):
+        group = int(rng.choice([32, 64, 128, 128, 128, 256]))
+        G = int(rng.integers(1, 41))
+        K = G * group
+        N = 8 * int(rng.integers(1, 160))
+        M = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 15, 16, 17, 31, 32, 33, 64, 65, 100, 128, 200]))
+        X, Wp, s, Zp = wl.make(M, K, N, index=5000 + case, group=group)
+        ref = orc.gemm(X, Wp, s, Zp, group)
+        fams = [binding.KERNEL_TILE] + ([binding.KERNEL_STRIPE] if M <= 16 else []) + ([binding.KERNEL_WAVE_SPLIT] if M <= 4 else [])
+        forced = (int(rng.choice(fams)), int(rng.integers(1, G + 1)))
+        for kernel, split in ((binding.KERNEL_AUTO, 0), forced):
+            say("random", case, (M, K, N, group), "kernel", kernel, "split", split)
+            Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=kernel, split=split)
+            r = err_ratio(Y, ref)
+            assert r <= 1.0, (case, M, K, N, group, kernel, split, r)
+
+
 def test_integer_case_bit_exact(gpu):
     """s = 1, z = 0, X in {-1,0,1}, K = 128: integers below 2048, exactly representable."""
     rng = np.random.default_rng(21)
