@@ -11,8 +11,8 @@ more than 640 MB, so that no step finds its weights in the 256 MB last-level
 cache ("cold"); --warm reuses one copy and is labelled so.
 
 Prints ONE JSON line on stdout (headline: M=1, K=28672, N=8192).  --table adds
-every configuration of the workload list to the line and writes it under
-gpurun_out/ as well.
+every configuration of the workload list to the line; --out DIR also writes the
+tables as JSON files into DIR.
 """
 from __future__ import annotations
 
@@ -42,6 +42,13 @@ def measured_traffic(key):
             return json.load(f).get(key, {}).get("bytes_per_launch")
     except (OSError, ValueError):
         return None
+
+
+def save(out_dir, name, obj):
+    if out_dir:
+        os.makedirs(out_dir, exist_ok=True)
+        with open(os.path.join(out_dir, name), "w") as f:
+            json.dump(obj, f, indent=1)
 
 
 def log(*a):
@@ -260,6 +267,7 @@ def main():
     ap.add_argument("--ablation", action="store_true",
                     help="also time the unfused variant (dequantised FP16 weights through HBM + vendor FP16 GEMM) "
                          "and the FP16 x FP16 GEMM alone against the fused path (Section 4.2)")
+    ap.add_argument("--out", default=None, help="directory for bench_table.json, bench_fig2.json, bench_ablation.json")
     ap.add_argument("--no-cpu", action="store_true", help="skip the host-baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -326,19 +334,13 @@ def main():
                 rows.append(r)
             del h
         line["table"] = rows
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
-            json.dump(line, f, indent=1)
+        save(args.out, "bench_table.json", line)
     if args.ablation:
         line["ablation"] = ablation(torch, binding, wl, args.steps)
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_ablation.json"), "w") as f:
-            json.dump(line["ablation"], f, indent=1)
+        save(args.out, "bench_ablation.json", line["ablation"])
     if args.fig2:
         line["fig2"] = fig2(torch, binding, wl, args.steps)
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_fig2.json"), "w") as f:
-            json.dump(line["fig2"], f, indent=1)
+        save(args.out, "bench_fig2.json", line["fig2"])
     print(json.dumps(line), flush=True)
 
 
