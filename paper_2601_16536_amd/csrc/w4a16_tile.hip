@@ -1,4 +1,5 @@
-// W4A16 multiply for M >= 5: one workgroup per (64-column tile, block of 16 RT
+// W4A16 multiply, any M (the scheduler's choice except for M <= 4 on large weight
+// matrices): one workgroup per (64-column tile, block of 16 RT
 // rows of X, K slice), RT = 1, 2 or 4.  The waves of a workgroup own contiguous
 // runs of the slice's K (Algorithm 1, Phase 2 with the slices held by waves) and
 // their results meet in LDS; with S = 1 the workgroup casts and stores Y itself,
@@ -17,10 +18,12 @@
 // than summing on the vector ALU while staging, which every column tile repeats).
 //
 // X reaches LDS per wave: a wave needs only the X of its own run of K, stages it
-// in double-buffered chunks of one or two blocks, and so never waits at a
-// workgroup barrier before the final sum.  Four lanes fetch the 64 contiguous
-// bytes a block takes of one row of X; the LDS rows are padded by four entries so
-// that these writes, and the MFMA's reads, are free of bank conflicts.
+// in double-buffered chunks of one, two or four blocks, and so never waits at a
+// workgroup barrier before the final sum.  Neighbouring lanes fetch contiguous
+// bytes of one row of X; the LDS rows are padded so that these writes, and the
+// MFMA's reads, are free of bank conflicts.  Two kernels follow: a loop over
+// single blocks for any group size, and one laid out around the group for
+// group = 128.
 //
 // The row blocks of one column tile read the same weights.  Workgroups are
 // numbered so that they sit on the same XCD (workgroup b runs on XCD b mod 8) and
