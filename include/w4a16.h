@@ -33,7 +33,8 @@
  * All data pointers are DEVICE pointers owned by the caller, 16-byte aligned;
  * the library neither keeps nor frees them.  `stream` is a hipStream_t passed
  * as void* (NULL = the default stream).  Calls only enqueue work on `stream`;
- * they never synchronise the device.
+ * the one exception is the call that makes the library allocate a split buffer
+ * (see w4a16_gemm), which waits for the device once.
  *
  * Errors: every function returns a w4a16_status (0 = success).  On any error
  * nothing is launched and Y is untouched.  Nothing aborts, throws or prints.
@@ -41,10 +42,11 @@
  * Shapes: M >= 1, N >= 8 with N % 8 == 0, K % group == 0, group a multiple of
  * 32 (the paper fixes no granularity for s and z; 128 is the tuned case).
  *
- * Threads: the library-owned workspace is one per device and is used by every
- * call on that device, so two calls that overlap in time on one device (on
- * different streams) race on it unless each passes its own workspace through
- * w4a16_gemm_ws.  Results are bitwise reproducible for a fixed shape and plan.
+ * Threads and streams: the library-owned split buffers are one set per device,
+ * used by every call on that device, so two calls that overlap in time on one
+ * device (on different streams) race on them unless each passes its own
+ * workspace through w4a16_gemm_ws.  Results are bitwise reproducible for a fixed
+ * shape and plan.
  */
 #ifndef W4A16_H
 #define W4A16_H
@@ -62,9 +64,9 @@ typedef enum {
     W4A16_ERR_SHAPE = 2,       /* M, N or K out of range, or N % 8 / K % 8 != 0        */
     W4A16_ERR_GROUP = 3,       /* group not a multiple of 32, or K % group != 0        */
     W4A16_ERR_ALIGN = 4,       /* a data pointer is not 16-byte aligned                */
-    W4A16_ERR_WORKSPACE = 5,   /* caller's workspace too small, or allocation failed   */
+    W4A16_ERR_WORKSPACE = 5,   /* workspace too small, allocation failed, or allocation needed during stream capture */
     W4A16_ERR_HIP = 6,         /* the HIP runtime reported an error on launch          */
-    W4A16_ERR_UNSUPPORTED = 7  /* forced kernel / split not valid for this shape       */
+    W4A16_ERR_UNSUPPORTED = 7  /* forced kernel / split not valid for this shape, or M*K*2 >= 2^31 bytes (32-bit offsets) */
 } w4a16_status;
 
 /* Kernel families the scheduler chooses from (Algorithm 1, Phase 2 is the
@@ -98,33 +100,60 @@ typedef struct {
 } w4a16_plan;
 
 /*
- * Y = X * s (W - z)   (Eq. 2), plan chosen by the library's Split-K scheduler,
- * partial sums in the library-owned workspace of the current device (grown with
- * hipMalloc on first need, kept until w4a16_shutdown).
+ * Y = X * s (W - z)   (Eq. 2), plan chosen by the library's Split-K scheduler.
+ * The split buffers of Algorithm 1 (Phase 2 writes them, Phase 3 adds them)
+ * are, in this order of preference: the workspace registered for the current
+ * device with w4a16_set_workspace; else library-owned buffers of that device,
+ * allocated with hipMalloc when a call first needs them (that call, and only
+ * that one, waits for the device while it clears the new buffer), grown when a
+ * later call needs more, kept until w4a16_shutdown and never freed before (work
+ * already enqueued, or recorded in a HIP graph, keeps pointing at valid
+ * memory).  While `stream` is being captured into a graph nothing can be
+ * allocated: a call that would have to returns W4A16_ERR_WORKSPACE; run the
+ * same shape once outside the capture first, or use w4a16_set_workspace or
+ * w4a16_gemm_ws.  If a launch fails
+ * (W4A16_ERR_HIP) the library clears its accumulator again before the next use.
  */
 int w4a16_gemm(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
                int group, int M, int N, int K, void *Y, void *stream);
 
 /*
- * The same with the plan forced: `kernel` is a w4a16_kernel (AUTO = choose),
- * `split` the split factor S (0 = choose; otherwise 1 <= S <= K/group; the
- * library may lower it so that no slice is empty).  For sweeps and tests.
+ * The same with Algorithm 1's inputs chosen by the caller: `kernel` is a
+ * w4a16_kernel (its block sizes; AUTO = choose), `split` the split factor S
+ * (0 = choose; otherwise 1 <= S <= K/group; the library lowers it so that no
+ * slice is empty, and raises it where a slice would not fit a workgroup's LDS
+ * or a 31-bit buffer: w4a16_query_plan tells).  For sweeps and tests.
  */
 int w4a16_gemm_ex(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
                   int group, int M, int N, int K, void *Y, void *stream, int kernel, int split);
 
 /*
- * The same, with the Split-K workspace brought by the caller: `workspace` is
- * device memory of at least the plan's workspace_bytes (w4a16_query_plan; for
- * the scheduler's own choice also w4a16_workspace_bytes), 256-byte aligned.
- * Its contents need no initialisation (a plan that uses it as accumulator clears it
- * with one small extra launch first).  Performs no allocation.
+ * The same, with the split buffers of Algorithm 1 (Section 3: the per-slice
+ * results C_i in global memory) brought by the caller for this one call:
+ * `workspace` is device memory of at least the plan's workspace_bytes
+ * (w4a16_query_plan; for the scheduler's own choice also
+ * w4a16_workspace_bytes), 256-byte aligned.  Its contents need no
+ * initialisation (a plan that uses it as accumulator clears it with one small
+ * extra launch first).  Performs no allocation and keeps no state: calls with
+ * different workspaces may overlap on one device.
  */
 int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
                   int group, int M, int N, int K, void *Y, void *stream, int kernel, int split,
                   void *workspace, size_t workspace_bytes);
 
-/* Workspace bytes of the plan the scheduler itself chooses for this shape (at least 256). */
+/*
+ * Registers caller-owned split buffers (Algorithm 1's C_i; Section 3) for the
+ * current device: device memory, 256-byte aligned, at least 256 bytes, owned by
+ * the caller and kept valid until it is replaced or removed (NULL removes it).
+ * w4a16_gemm and w4a16_gemm_ex then use it instead of library-owned buffers and
+ * never allocate; a plan that needs more than `workspace_bytes` returns
+ * W4A16_ERR_WORKSPACE.  As with w4a16_gemm_ws the contents need no
+ * initialisation.  Calls that overlap in time on one device share it and race.
+ */
+int w4a16_set_workspace(void *workspace, size_t workspace_bytes);
+
+/* Bytes of split buffers (Section 3) that the plan the scheduler itself chooses for this shape needs (at least
+ * 256); forced plans: w4a16_query_plan. */
 size_t w4a16_workspace_bytes(int M, int N, int K, int group);
 
 /* The plan w4a16_gemm_ex would run for these arguments (no launch, no GPU call
@@ -152,14 +181,30 @@ int w4a16_dequant(const uint32_t *Wpacked, const void *scales, const uint32_t *z
 int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, void *scales, uint32_t *zeros,
                    void *stream);
 
+/*
+ * Tuning knobs, for sweeps and tests only: process-wide state that changes the plans of every later call
+ * (w4a16_query_plan reports them as changed).  Each knob starts from the environment variable W4A16_<KNOB IN
+ * CAPITALS>, read once when the library first plans a call; 0 restores the scheduler's own choice.
+ *   "stripe_finish"  1: K slices of different workgroups always meet in the accumulator, 2: always second pass
+ *   "stripe_waves"   waves per STRIPE workgroup
+ *   "stripe_dyn"     M <= 4: 2 = equal contiguous runs per wave instead of units handed out by ticket
+ *   "stripe_unit"    packed rows per unit handed out (2 or 4)
+ *   "stripe_depth"   units in flight per wave (1..4)
+ *   "tile_rows"      rows of X per TILE workgroup (16, 32, 64)
+ *   "tile_waves"     waves per TILE workgroup (4..8)
+ *   "log"            1: every w4a16_gemm* call prints its plan on stderr (the one case in which the library prints)
+ * Returns W4A16_ERR_UNSUPPORTED for an unknown knob.
+ */
+int w4a16_tune(const char *knob, int value);
+
 /* Text for a status code (static storage). */
 const char *w4a16_status_string(int status);
 
 /* Text of the last HIP error seen by this thread's failing call ("" if none). */
 const char *w4a16_last_hip_error(void);
 
-/* Frees the library-owned workspaces of all devices.  Call only when no
- * w4a16 work is in flight. */
+/* Frees the library-owned split buffers of all devices.  Call only when no
+ * w4a16 work is in flight and no HIP graph that recorded w4a16 calls will be replayed. */
 void w4a16_shutdown(void);
 
 #ifdef __cplusplus

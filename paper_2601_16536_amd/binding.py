@@ -16,7 +16,8 @@ ERR_NULL, ERR_SHAPE, ERR_GROUP, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORT
 KERNEL_AUTO, KERNEL_WAVE_SPLIT, KERNEL_STRIPE, KERNEL_TILE = -1, 0, 3, 4  # 1 and 2: retired families
 
 EXPORTS = (
-    "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_workspace_bytes", "w4a16_query_plan",
+    "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_set_workspace", "w4a16_tune",
+    "w4a16_workspace_bytes", "w4a16_query_plan",
     "w4a16_reduce", "w4a16_dequant", "w4a16_quantize", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
 )
 
@@ -63,6 +64,8 @@ def lib():
         L.w4a16_gemm.argtypes = gemm_args
         L.w4a16_gemm_ex.argtypes = gemm_args + [ci, ci]
         L.w4a16_gemm_ws.argtypes = gemm_args + [ci, ci, vp, sz]
+        L.w4a16_set_workspace.argtypes = [vp, sz]
+        L.w4a16_tune.argtypes = [ctypes.c_char_p, ci]
         L.w4a16_workspace_bytes.argtypes = [ci, ci, ci, ci]
         L.w4a16_workspace_bytes.restype = sz
         L.w4a16_query_plan.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(Plan)]
@@ -122,6 +125,24 @@ def raw_gemm_ex(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, k
 def raw_gemm_ws(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel, split, ws_ptr, ws_bytes) -> int:
     return lib().w4a16_gemm_ws(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel, split,
                                ws_ptr, ws_bytes)
+
+
+def set_workspace(workspace) -> None:
+    """Registers a caller-owned workspace tensor (uint8, CUDA, 256-byte aligned) for the current device; None removes it.
+    The tensor must stay alive while it is registered."""
+    if workspace is None:
+        rc = lib().w4a16_set_workspace(None, 0)
+    else:
+        rc = lib().w4a16_set_workspace(workspace.data_ptr(), workspace.numel() * workspace.element_size())
+    if rc:
+        raise W4A16Error(rc, "w4a16_set_workspace")
+
+
+def tune(knob: str, value: int) -> None:
+    """Sets a tuning knob of the library (sweeps and tests only); 0 restores the scheduler's choice."""
+    rc = lib().w4a16_tune(knob.encode(), int(value))
+    if rc:
+        raise W4A16Error(rc, "w4a16_tune(%r)" % knob)
 
 
 def gemm(X, Wpacked, scales, zeros, group: int, out=None, stream=None):

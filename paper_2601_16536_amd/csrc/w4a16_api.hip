@@ -5,9 +5,11 @@
 #include "../../include/w4a16.h"
 #include "w4a16_internal.h"
 
+#include <cstdio>
 #include <cstdlib>
 #include <mutex>
 #include <string.h>
+#include <vector>
 
 namespace {
 
@@ -19,8 +21,12 @@ struct DeviceState {
     int cus = 0;             // compute units (0 = not read yet)
     void *ws = nullptr;      // library-owned workspace (fp32 partials of the two-pass plans)
     size_t ws_bytes = 0;
-    void *acc = nullptr;     // library-owned fixed-point accumulator of the STRIPE and TILE families: all zero between calls
+    void *acc = nullptr;     // library-owned fixed-point accumulator: all zero between calls
     size_t acc_bytes = 0;
+    bool acc_dirty = false;  // a launch that used it failed: cleared again before the next use
+    std::vector<void *> retired;  // outgrown buffers: work already enqueued (or captured in a graph) may still use them
+    void *user_ws = nullptr;      // w4a16_set_workspace: the caller's split buffers for this device
+    size_t user_ws_bytes = 0;
 };
 
 std::mutex g_mutex;
@@ -32,6 +38,48 @@ void note_hip_error(hipError_t e)
     const char *s = hipGetErrorString(e);
     strncpy(t_hip_error, s ? s : "unknown HIP error", sizeof(t_hip_error) - 1);
     t_hip_error[sizeof(t_hip_error) - 1] = 0;
+}
+
+// ---- tuning knobs (for sweeps and tests only) ----------------------------------
+//
+// Process-wide; each starts from the environment variable of the same name in capitals with the prefix
+// W4A16_ (read once, when the library first needs it) and can be changed with w4a16_tune.  0 = the
+// scheduler's own choice.
+struct Tuning {
+    int stripe_finish = 0;  // 1: slices always meet in the accumulator, 2: always in the workspace + second pass
+    int stripe_waves = 0;   // waves per STRIPE workgroup
+    int stripe_dyn = 0;     // M <= 4: 0/1 = units handed out by ticket (the default), 2 = equal contiguous runs per wave
+    int stripe_unit = 0;    // packed rows per unit of the ticket form (2 or 4)
+    int stripe_depth = 0;   // units in flight per wave of the ticket form (1..4)
+    int tile_rows = 0;      // rows of X per TILE workgroup (16, 32, 64)
+    int tile_waves = 0;     // waves per TILE workgroup (4..8)
+    int log = 0;            // 1: every call prints its plan on stderr
+};
+
+struct Knob {
+    const char *name;
+    int Tuning::*field;
+};
+const Knob kKnobs[] = {
+    {"stripe_finish", &Tuning::stripe_finish}, {"stripe_waves", &Tuning::stripe_waves}, {"stripe_dyn", &Tuning::stripe_dyn},
+    {"stripe_unit", &Tuning::stripe_unit},     {"stripe_depth", &Tuning::stripe_depth}, {"tile_rows", &Tuning::tile_rows},
+    {"tile_waves", &Tuning::tile_waves},       {"log", &Tuning::log},
+};
+
+Tuning &tuning()
+{
+    static Tuning t = [] {
+        Tuning v;
+        for (const Knob &k : kKnobs) {
+            char env[64] = "W4A16_";
+            size_t n = strlen(env);
+            for (const char *c = k.name; *c && n + 1 < sizeof env; ++c) env[n++] = (char)(*c >= 'a' && *c <= 'z' ? *c - 32 : *c);
+            env[n] = 0;
+            if (const char *e = getenv(env)) v.*(k.field) = atoi(e);
+        }
+        return v;
+    }();
+    return t;
 }
 
 // Current device index, or -1 when no GPU is usable (planning still works then,
@@ -72,14 +120,20 @@ int check_shape(int group, int M, int N, int K)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// The kernels address X, and a K slice of the weights, with 32-bit byte offsets.
+bool fits_32bit_offsets(int M, int N, int K, int group, int gps)
+{
+    return (unsigned long long)M * K * 2ull < 0x7F000000ull && (unsigned long long)gps * (group / 8) * N * 4ull < 0x7F000000ull;
+}
+
 // ---- the Split-K scheduler ---------------------------------------------------
 //
 // Algorithm 1 takes the split factor S and the block sizes as inputs.  Here the
 // scheduler (kernel = AUTO, split = 0) chooses them from the shape alone:
 //
 // STRIPE (M <= 2 from about 10 MB of packed weights on, M <= 4 from about 48 MB on): 256-column stripes
-//   x S slices of K with S = compute units / stripes, rounded down: one workgroup per compute unit; ten
-//   to sixteen waves of a workgroup own contiguous runs of the slice's rows.
+//   x S slices of K with S = compute units / stripes, rounded down: one workgroup per compute unit whose
+//   waves share the slice.
 // TILE (everything else): 64-column tiles x 16, 32 or 64 rows of X per workgroup (as many rows as still
 //   leave a workgroup per compute unit at S = 1), eight waves own contiguous runs of the slice's K;
 //   S = compute units / workgroups, rounded down (a workgroup too many would run as a second round).
@@ -96,11 +150,9 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // second pass.  Measured crossover: between 0.5 M and 1 M adds.  The other families always take the second pass.
 bool slices_meet_in_accumulator(int M, int N, int S)
 {
-    if (S > 255) return false;
-    if (const char *e = getenv("W4A16_STRIPE_FINISH")) {  // tuning aid for sweeps, not part of the contract
-        if (e[0] == 'a') return true;
-        if (e[0] == 'w') return false;
-    }
+    if (S > 63) return false;  // the accumulator counts arrivals in six bits
+    if (tuning().stripe_finish == 1) return true;
+    if (tuning().stripe_finish == 2) return false;
     return (long long)S * M * N <= 640 * 1024;
 }
 
@@ -121,11 +173,20 @@ size_t workspace_of(int kernel, int M, int N, int S)
     }
 }
 
+bool stripe_by_ticket(int M) { return M <= 4 && tuning().stripe_dyn != 2; }
+
+// LDS a STRIPE workgroup needs for a slice of gps groups, and the most it may use.
+size_t stripe_lds(int M, int group, int gps, int waves)
+{
+    return stripe_by_ticket(M) ? stripe_dyn_lds_bytes(M, group, gps) : stripe_lds_bytes(M, group, gps, waves);
+}
+size_t stripe_lds_max(int M) { return (size_t)(stripe_by_ticket(M) ? stripe_dyn_lds_limit() : stripe_lds_limit()); }
+
 int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4a16_plan *p)
 {
     const int G = K / group;
     if (kernel == W4A16_KERNEL_AUTO) {
-        // STRIPE streams large weight matrices about 8 % faster than TILE, but its 256-column stripes need four
+        // STRIPE streams large weight matrices faster than TILE, but its 256-column stripes need four
         // times the slices, hence four times the atomic adds (S M N), and it carries more fixed cost.
         // Measured on sixteen shapes from 2 MB to 117 MB of packed weights: STRIPE wins for M <= 2 from about
         // 10 MB on, for M = 3, 4 only from about 48 MB on; TILE everywhere else.
@@ -145,36 +206,34 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->tile_n = 256;
         p->tile_m = M <= 4 ? 4 : 16;
         tiles = (N + 255) / 256;
+        if (tiles > 65535) return W4A16_ERR_UNSUPPORTED;  // a grid dimension
         const int wmin = stripe_min_waves(M), wmax = stripe_max_waves(M);
         if (S == 0) S = (int)(cus / tiles);  // at most one workgroup per compute unit (measured, N = 14336: 280 workgroups 11.4 us, 224 8.9 us)
         if (S < 1) S = 1;
         if (S > G) S = G;
         int gps = (G + S - 1) / S;
-        // the slice's X rows must fit the workgroup's LDS and its weights a 31-bit buffer: shorten the slice if not
-        while (gps > 1 && (stripe_lds_bytes(M, group, gps, wmin) > (size_t)stripe_lds_limit() ||
-                           (unsigned long long)gps * (group / 8) * N * 4ull >= 0x7F000000ull))
+        // the slice's X rows (and, handed out by ticket, its scales) must fit the workgroup's LDS and its weights a
+        // 31-bit buffer: shorten the slice if not
+        while (gps > 1 && (stripe_lds(M, group, gps, wmin) > stripe_lds_max(M) || !fits_32bit_offsets(1, N, 8, group, gps)))
             gps = (gps + 1) / 2;
         S = (G + gps - 1) / gps;
-        if (stripe_lds_bytes(M, group, gps, wmin) > (size_t)stripe_lds_limit()) return W4A16_ERR_UNSUPPORTED;
-        if (S > 65535) return W4A16_ERR_UNSUPPORTED;  // the slices are the grid's second dimension
+        if (stripe_lds(M, group, gps, wmin) > stripe_lds_max(M)) return W4A16_ERR_UNSUPPORTED;
+        if (S > 65535) return W4A16_ERR_UNSUPPORTED;  // a grid dimension of the many-row form
         // waves: each should own at least four blocks of 16 k; twelve measured best on the large shapes for
         // M <= 4 (ten to sixteen are within 3 % of each other); the many-row form holds eight at most
         const long long nblocks = (long long)gps * (group / 16);
         int waves = (int)(nblocks / 4);
         const int wbest = wmax > 12 ? 12 : wmax;
         waves = waves < wmin ? wmin : (waves > wbest ? wbest : waves);
-        if (const char *e = getenv("W4A16_STRIPE_WAVES")) {  // tuning aid for sweeps, not part of the contract
-            const int w = atoi(e);
-            if (w >= wmin && w <= wmax) waves = w;
-        }
-        while (waves > wmin && stripe_lds_bytes(M, group, gps, waves) > (size_t)stripe_lds_limit()) --waves;
+        if (tuning().stripe_waves >= wmin && tuning().stripe_waves <= wmax) waves = tuning().stripe_waves;
+        while (waves > wmin && stripe_lds(M, group, gps, waves) > stripe_lds_max(M)) --waves;
         p->waves_k = waves;
         p->threads = waves * 64;
         p->split = S;
         p->groups_per_split = gps;
         p->workgroups = (int)(tiles * S);
         p->workspace_bytes = workspace_of(kernel, M, N, S);
-        return W4A16_OK;
+        return fits_32bit_offsets(M, N, K, group, gps) ? W4A16_OK : W4A16_ERR_UNSUPPORTED;
     }
     if (kernel == W4A16_KERNEL_TILE) {
         p->tile_n = 64;
@@ -186,27 +245,24 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         // the FP32 partials and the second pass).
         int rows_x = 64;
         while (rows_x > 16 && (rows_x / 2 >= M || tiles * ((M + rows_x - 1) / rows_x) < cus)) rows_x /= 2;
-        if (const char *e = getenv("W4A16_TILE_ROWS")) {  // tuning aid for sweeps, not part of the contract
-            const int r = atoi(e);
-            if (r == 16 || r == 32 || r == 64) rows_x = r;
-        }
+        const int tr = tuning().tile_rows;
+        if (tr == 16 || tr == 32 || tr == 64) rows_x = tr;
         p->tile_m = rows_x;
-        if (const char *e = getenv("W4A16_TILE_WAVES")) {  // tuning aid for sweeps, not part of the contract
-            const int w = atoi(e);
-            if (w >= 4 && w <= 8) { p->waves_k = w; p->threads = 64 * w; }
-        }
+        const int tw = tuning().tile_waves;
+        if (tw >= 4 && tw <= 8) { p->waves_k = tw; p->threads = 64 * tw; }
         const long long wgs = tiles * ((M + rows_x - 1) / rows_x);
         if (S == 0) S = (int)(cus / wgs);  // never more workgroups than compute units: the extra ones would run as a second round
         if (S < 1) S = 1;
         if (S > G) S = G;
         int gps = (G + S - 1) / S;
-        while (gps > 1 && (unsigned long long)gps * (group / 8) * N * 4ull >= 0x7F000000ull) gps = (gps + 1) / 2;
+        while (gps > 1 && !fits_32bit_offsets(1, N, 8, group, gps)) gps = (gps + 1) / 2;
         S = (G + gps - 1) / gps;
         p->split = S;
         p->groups_per_split = gps;
         p->workgroups = (int)(wgs * S);
         p->workspace_bytes = workspace_of(kernel, M, N, S);
-        return W4A16_OK;
+        if (((long long)tiles * S + 7) / 8 * 8 * ((M + rows_x - 1) / rows_x) > 0x7FFFFFFFLL) return W4A16_ERR_UNSUPPORTED;
+        return fits_32bit_offsets(M, N, K, group, gps) ? W4A16_OK : W4A16_ERR_UNSUPPORTED;
     }
     {  // WAVE_SPLIT
         p->tile_n = (N + 63) / 64 >= cus ? 64 : 32;
@@ -214,6 +270,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->waves_k = 16;
         p->threads = 1024;
         tiles = (N + p->tile_n - 1) / p->tile_n;
+        if (tiles > 65535) return W4A16_ERR_UNSUPPORTED;  // a grid dimension
         if (S == 0) {
             // One launch unless the tiles cover at most a quarter of the compute units AND each
             // workgroup would still stream at least 128 KiB per slice (below that the second
@@ -230,74 +287,130 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
     if (S > G) S = G;
     int gps = (G + S - 1) / S;
     // slices keep 32-bit buffer offsets: raise S until a slice is below ~2 GiB
-    while ((unsigned long long)gps * (group / 8) * N * 4ull >= 0x7F000000ull && gps > 1) gps = (gps + 1) / 2;
+    while (gps > 1 && !fits_32bit_offsets(1, N, 8, group, gps)) gps = (gps + 1) / 2;
     S = (G + gps - 1) / gps;  // no empty slice
     p->split = S;
     p->groups_per_split = gps;
     p->workgroups = (int)(tiles * S);
     p->workspace_bytes = workspace_of(kernel, M, N, S);
-    return W4A16_OK;
+    return fits_32bit_offsets(M, N, K, group, gps) ? W4A16_OK : W4A16_ERR_UNSUPPORTED;
 }
 
-int ensure_workspace(int dev, size_t bytes, void **out)
+// ---- split buffers --------------------------------------------------------------
+
+// True when `stream` is being captured into a graph: nothing may be allocated or synchronised then.
+bool capturing(hipStream_t stream)
 {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    DeviceState &d = g_dev[dev];
-    if (d.ws_bytes < bytes) {
-        if (d.ws) {
-            // hipFree waits for the device, so work still using the old buffer has drained
-            hipError_t e = hipFree(d.ws);
-            d.ws = nullptr;
-            d.ws_bytes = 0;
-            if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_WORKSPACE; }
-        }
-        size_t want = bytes + bytes / 4;
-        void *ptr = nullptr;
-        hipError_t e = hipMalloc(&ptr, want);
-        if (e != hipSuccess) { note_hip_error(e); (void)hipGetLastError(); return W4A16_ERR_WORKSPACE; }
-        d.ws = ptr;
-        d.ws_bytes = want;
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
     }
-    *out = d.ws;
-    return W4A16_OK;
+    return st != hipStreamCaptureStatusNone;
 }
 
-// The accumulator of the STRIPE and TILE families: grown on demand, cleared once when allocated (on `stream`,
-// ahead of the launch that first uses it); every launch leaves it all zero again.
-int ensure_accumulator(int dev, size_t bytes, hipStream_t stream, void **out)
+// Grows one of the library-owned buffers.  The old buffer is not freed: work enqueued earlier, or recorded in a
+// graph, may still use it; it goes to the retired list until w4a16_shutdown.  Never called during stream capture.
+int grow(DeviceState &d, void **buf, size_t *have, size_t bytes, size_t floor_bytes, bool zeroed)
 {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    DeviceState &d = g_dev[dev];
-    if (d.acc_bytes < bytes) {
-        if (d.acc) {
-            hipError_t e = hipFree(d.acc);
-            d.acc = nullptr;
-            d.acc_bytes = 0;
-            if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_WORKSPACE; }
-        }
-        size_t want = bytes < (1u << 20) ? (1u << 20) : bytes + bytes / 4;
-        void *ptr = nullptr;
-        hipError_t e = hipMalloc(&ptr, want);
-        if (e != hipSuccess) { note_hip_error(e); (void)hipGetLastError(); return W4A16_ERR_WORKSPACE; }
-        e = launch_accumulator_clear(static_cast<unsigned long long *>(ptr), want / 8, stream);
+    size_t want = bytes + bytes / 4;
+    if (want < floor_bytes) want = floor_bytes;
+    void *ptr = nullptr;
+    hipError_t e = hipMalloc(&ptr, want);
+    if (e != hipSuccess) { note_hip_error(e); (void)hipGetLastError(); return W4A16_ERR_WORKSPACE; }
+    if (zeroed) {
+        // cleared before any stream can see it: the copy engine's memset, then a wait for the device
+        e = hipMemset(ptr, 0, want);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) { note_hip_error(e); (void)hipFree(ptr); return W4A16_ERR_HIP; }
-        d.acc = ptr;
-        d.acc_bytes = want;
     }
-    *out = d.acc;
+    if (*buf) d.retired.push_back(*buf);
+    *buf = ptr;
+    *have = want;
     return W4A16_OK;
 }
 
-int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *zeros, int group, int M, int N, int K,
-        void *Y, void *stream, int kernel, int split, void *user_ws, size_t user_ws_bytes, bool user_ws_given)
+enum Source { kFromLibrary, kFromCall };
+
+struct Buffers {
+    unsigned long long *sync = nullptr;  // the accumulator: zero before the launch, left zero by it
+    float *partials = nullptr;
+    bool library_acc = false;
+};
+
+int find_buffers(int dev, const w4a16_plan &plan, int finish, int M, int N, hipStream_t st, Source src, void *call_ws,
+                 size_t call_ws_bytes, Buffers *out)
+{
+    if (finish == kFinishDirect) return W4A16_OK;
+    void *given = nullptr;
+    size_t given_bytes = 0;
+    if (src == kFromCall) {
+        given = call_ws;
+        given_bytes = call_ws_bytes;
+    } else {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        if (g_dev[dev].user_ws) {
+            given = g_dev[dev].user_ws;
+            given_bytes = g_dev[dev].user_ws_bytes;
+        }
+    }
+    if (given) {
+        if (given_bytes < plan.workspace_bytes) return W4A16_ERR_WORKSPACE;
+        if (finish == kFinishAccumulator) {  // contents unknown: cleared by a small launch first
+            out->sync = static_cast<unsigned long long *>(given);
+            hipError_t e = launch_accumulator_clear(out->sync, (size_t)M * N, st);
+            if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+        } else {
+            out->partials = static_cast<float *>(given);
+        }
+        return W4A16_OK;
+    }
+    // library-owned, grown on demand
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState &d = g_dev[dev];
+    if (finish == kFinishAccumulator) {
+        if (d.acc_bytes < plan.workspace_bytes) {
+            if (capturing(st)) return W4A16_ERR_WORKSPACE;
+            int rc = grow(d, &d.acc, &d.acc_bytes, plan.workspace_bytes, 1u << 20, true);
+            if (rc) return rc;
+            d.acc_dirty = false;
+        }
+        out->sync = static_cast<unsigned long long *>(d.acc);
+        out->library_acc = true;
+        if (d.acc_dirty) {
+            hipError_t e = launch_accumulator_clear(out->sync, d.acc_bytes / 8, st);
+            if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+            d.acc_dirty = false;
+        }
+    } else {
+        if (d.ws_bytes < plan.workspace_bytes) {
+            if (capturing(st)) return W4A16_ERR_WORKSPACE;
+            int rc = grow(d, &d.ws, &d.ws_bytes, plan.workspace_bytes, 0, false);
+            if (rc) return rc;
+        }
+        out->partials = static_cast<float *>(d.ws);
+    }
+    return W4A16_OK;
+}
+
+void log_plan(const char *entry, int M, int N, int K, int group, const w4a16_plan &p, int finish)
+{
+    static const char *const kFinish[] = {"direct", "accumulator", "second pass"};
+    fprintf(stderr, "w4a16: %s M=%d N=%d K=%d group=%d -> kernel=%d S=%d groups/slice=%d tile=%dx%d waves=%d workgroups=%d finish=%s workspace=%zu\n",
+            entry, M, N, K, group, p.kernel, p.split, p.groups_per_split, p.tile_m, p.tile_n, p.waves_k, p.workgroups,
+            kFinish[finish], p.workspace_bytes);
+}
+
+int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales, const uint32_t *zeros, int group, int M, int N,
+        int K, void *Y, void *stream, int kernel, int split, Source src, void *call_ws, size_t call_ws_bytes)
 {
     t_hip_error[0] = 0;
     if (!X || !Wp || !scales || !zeros || !Y) return W4A16_ERR_NULL;
-    if (user_ws_given && !user_ws) return W4A16_ERR_NULL;
+    if (src == kFromCall && !call_ws) return W4A16_ERR_NULL;
     int rc = check_shape(group, M, N, K);
     if (rc) return rc;
     if (!aligned16(X) || !aligned16(Wp) || !aligned16(scales) || !aligned16(zeros) || !aligned16(Y)) return W4A16_ERR_ALIGN;
-    if (user_ws_given && (reinterpret_cast<uintptr_t>(user_ws) & 255u)) return W4A16_ERR_ALIGN;
+    if (src == kFromCall && (reinterpret_cast<uintptr_t>(call_ws) & 255u)) return W4A16_ERR_ALIGN;
 
     const int dev = current_device();
     if (dev < 0) { note_hip_error(hipErrorNoDevice); return W4A16_ERR_HIP; }
@@ -307,28 +420,10 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int finish = finish_of(plan.kernel, M, N, plan.split);
-    unsigned long long *sync = nullptr;  // the accumulator: zero before the launch, left zero by it
-    float *partials = nullptr;
-    if (user_ws_given && user_ws_bytes < plan.workspace_bytes) return W4A16_ERR_WORKSPACE;
-    if (finish == kFinishAccumulator) {
-        if (user_ws_given) {  // a caller's workspace comes uninitialised
-            sync = static_cast<unsigned long long *>(user_ws);
-            hipError_t e = launch_accumulator_clear(sync, (size_t)M * N, st);
-            if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
-        } else {
-            void *ptr = nullptr;
-            rc = ensure_accumulator(dev, plan.workspace_bytes, st, &ptr);
-            if (rc) return rc;
-            sync = static_cast<unsigned long long *>(ptr);
-        }
-    } else if (finish == kFinishSecondPass) {
-        void *ptr = user_ws;
-        if (!user_ws_given) {
-            rc = ensure_workspace(dev, plan.workspace_bytes, &ptr);
-            if (rc) return rc;
-        }
-        partials = static_cast<float *>(ptr);
-    }
+    if (tuning().log) log_plan(entry, M, N, K, group, plan, finish);
+    Buffers b;
+    rc = find_buffers(dev, plan, finish, M, N, st, src, call_ws, call_ws_bytes, &b);
+    if (rc) return rc;
 
     GemmArgs a;
     a.X = static_cast<const uint16_t *>(X);
@@ -336,19 +431,31 @@ int run(const void *X, const uint32_t *Wp, const void *scales, const uint32_t *z
     a.scales = static_cast<const uint16_t *>(scales);
     a.Zp = zeros;
     a.Y = static_cast<uint16_t *>(Y);
-    a.partials = partials;
+    a.partials = b.partials;
     a.group = group; a.M = M; a.N = N; a.K = K;
     a.split = plan.split;
     a.groups_per_split = plan.groups_per_split;
     a.groups = K / group;
 
-    hipError_t e = plan.kernel == W4A16_KERNEL_STRIPE       ? launch_stripe(a, finish, sync, plan.waves_k, st)
-                   : plan.kernel == W4A16_KERNEL_TILE       ? launch_tile(a, finish, sync, plan.tile_m, plan.waves_k, st)
-                                                            : launch_wave_split(a, plan.tile_n, st);
-    if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
-    if (finish == kFinishSecondPass) {
-        e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);
-        if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+    hipError_t e;
+    if (plan.kernel == W4A16_KERNEL_STRIPE && stripe_by_ticket(M)) {
+        const int unit = tuning().stripe_unit == 4 ? 4 : 2, depth = tuning().stripe_depth >= 1 && tuning().stripe_depth <= 4 ? tuning().stripe_depth : 2;
+        e = launch_stripe_dyn(a, finish, b.sync, plan.waves_k, unit, depth, st);
+    } else if (plan.kernel == W4A16_KERNEL_STRIPE) {
+        e = launch_stripe(a, finish, b.sync, plan.waves_k, st);
+    } else if (plan.kernel == W4A16_KERNEL_TILE) {
+        e = launch_tile(a, finish, b.sync, plan.tile_m, plan.waves_k, st);
+    } else {
+        e = launch_wave_split(a, plan.tile_n, st);
+    }
+    if (e == hipSuccess && finish == kFinishSecondPass) e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);
+    if (e != hipSuccess) {
+        note_hip_error(e);
+        if (b.library_acc) {  // what the failed launch left in the accumulator is unknown
+            std::lock_guard<std::mutex> lock(g_mutex);
+            g_dev[dev].acc_dirty = true;
+        }
+        return W4A16_ERR_HIP;
     }
     return W4A16_OK;
 }
@@ -360,19 +467,31 @@ extern "C" {
 int w4a16_gemm(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int M,
                int N, int K, void *Y, void *stream)
 {
-    return run(X, Wpacked, scales, zeros, group, M, N, K, Y, stream, W4A16_KERNEL_AUTO, 0, nullptr, 0, false);
+    return run("gemm", X, Wpacked, scales, zeros, group, M, N, K, Y, stream, W4A16_KERNEL_AUTO, 0, kFromLibrary, nullptr, 0);
 }
 
 int w4a16_gemm_ex(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int M,
                   int N, int K, void *Y, void *stream, int kernel, int split)
 {
-    return run(X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, nullptr, 0, false);
+    return run("gemm_ex", X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, kFromLibrary, nullptr, 0);
 }
 
 int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int M,
                   int N, int K, void *Y, void *stream, int kernel, int split, void *workspace, size_t workspace_bytes)
 {
-    return run(X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, workspace, workspace_bytes, true);
+    return run("gemm_ws", X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, kFromCall, workspace, workspace_bytes);
+}
+
+int w4a16_set_workspace(void *workspace, size_t workspace_bytes)
+{
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return W4A16_ERR_ALIGN;
+    if (workspace && workspace_bytes < 256) return W4A16_ERR_WORKSPACE;
+    const int dev = current_device();
+    if (dev < 0) { note_hip_error(hipErrorNoDevice); return W4A16_ERR_HIP; }
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_dev[dev].user_ws = workspace;
+    g_dev[dev].user_ws_bytes = workspace ? workspace_bytes : 0;
+    return W4A16_OK;
 }
 
 size_t w4a16_workspace_bytes(int M, int N, int K, int group)
@@ -389,6 +508,17 @@ int w4a16_query_plan(int M, int N, int K, int group, int kernel, int split, w4a1
     int rc = check_shape(group, M, N, K);
     if (rc) return rc;
     return make_plan(M, N, K, group, kernel, split, compute_units(current_device()), out);
+}
+
+int w4a16_tune(const char *knob, int value)
+{
+    if (!knob) return W4A16_ERR_NULL;
+    for (const Knob &k : kKnobs)
+        if (strcmp(knob, k.name) == 0) {
+            tuning().*(k.field) = value;
+            return W4A16_OK;
+        }
+    return W4A16_ERR_UNSUPPORTED;
 }
 
 int w4a16_reduce(const float *partials, int S, int M, int N, void *Y, void *stream)
@@ -438,9 +568,9 @@ const char *w4a16_status_string(int status)
     case W4A16_ERR_SHAPE: return "bad shape (need M >= 1, N % 8 == 0, K % 8 == 0)";
     case W4A16_ERR_GROUP: return "bad group (need group % 32 == 0 and K % group == 0)";
     case W4A16_ERR_ALIGN: return "pointer not aligned (16 bytes for data, 256 for a workspace)";
-    case W4A16_ERR_WORKSPACE: return "workspace too small or allocation failed";
+    case W4A16_ERR_WORKSPACE: return "workspace too small, or it would have to be allocated while the stream is being captured, or allocation failed";
     case W4A16_ERR_HIP: return "HIP runtime error";
-    case W4A16_ERR_UNSUPPORTED: return "forced kernel or split not valid for this shape";
+    case W4A16_ERR_UNSUPPORTED: return "forced kernel or split not valid for this shape, or the shape is beyond the kernels' 32-bit offsets";
     default: return "unknown status";
     }
 }
@@ -451,17 +581,21 @@ void w4a16_shutdown(void)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     for (int d = 0; d < kMaxDevices; ++d) {
-        if (!g_dev[d].ws && !g_dev[d].acc) continue;
+        DeviceState &s = g_dev[d];
+        if (!s.ws && !s.acc && s.retired.empty()) continue;
         int prev = -1;
         if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(d) == hipSuccess) {
-            if (g_dev[d].ws) (void)hipFree(g_dev[d].ws);
-            if (g_dev[d].acc) (void)hipFree(g_dev[d].acc);
+            if (s.ws) (void)hipFree(s.ws);
+            if (s.acc) (void)hipFree(s.acc);
+            for (void *p : s.retired) (void)hipFree(p);
             (void)hipSetDevice(prev);
         }
-        g_dev[d].ws = nullptr;
-        g_dev[d].ws_bytes = 0;
-        g_dev[d].acc = nullptr;
-        g_dev[d].acc_bytes = 0;
+        s.ws = nullptr;
+        s.ws_bytes = 0;
+        s.acc = nullptr;
+        s.acc_bytes = 0;
+        s.acc_dirty = false;
+        s.retired.clear();
     }
 }
 

@@ -7,27 +7,53 @@
 
 namespace w4a16 {
 
-// Fixed-point form of a slice sum for the cross-workgroup accumulator: the value
-// in units of 2^-24 (clamped far outside the FP16 range), biased to be positive,
-// in bits 0-55; one arrival in bits 56-63.  Up to 255 slices cannot carry into
-// the count.
+// Fixed-point form of a slice sum for the cross-workgroup accumulator, one 64-bit word per output:
+//   bits  0-56  the sum of the slices' values in units of 2^-24, each clamped to +-2^25 (far outside the FP16
+//               range, so that slice sums of a few million that cancel each other still add up right) and
+//               biased by 2^50 to be positive: 63 slices stay below 2^57;
+//   bit   57    set (by an atomic OR that precedes its slice's add) when a slice sum is NaN: the result is NaN;
+//   bits 58-63  arrivals: up to 63 slices.
 constexpr float kFixScale = 16777216.0f;            // 2^24
-constexpr float kFixClamp = 2097152.0f;             // 2^21
-constexpr unsigned long long kFixBias = 1ull << 46;
-constexpr unsigned long long kFixOne = 1ull << 56;
+constexpr float kFixClamp = 33554432.0f;            // 2^25
+constexpr int kFixMaxSlices = 63;
+constexpr unsigned long long kFixBias = 1ull << 50;
+constexpr unsigned long long kFixPoison = 1ull << 57;
+constexpr unsigned long long kFixOne = 1ull << 58;
+constexpr uint16_t kHalfNaN = 0x7E00u;
 
+// A slice sum that is not NaN.
 __device__ __forceinline__ unsigned long long to_fixed(float v)
 {
     v = fminf(fmaxf(v, -kFixClamp), kFixClamp);
-    const long long fx = (long long)__builtin_rintf(v * kFixScale);  // |v| <= 2^21: the product is exact, |fx| <= 2^45
+    const long long fx = (long long)__builtin_rintf(v * kFixScale);  // |v| <= 2^25: the product is exact, |fx| <= 2^49
+    return (unsigned long long)(fx + (long long)kFixBias) + kFixOne;
+}
+
+// The same from a sum already in units of 2^-24.
+__device__ __forceinline__ unsigned long long to_fixed(long long fx)
+{
+    constexpr long long lim = 1ll << 49;
+    fx = fx < -lim ? -lim : (fx > lim ? lim : fx);
     return (unsigned long long)(fx + (long long)kFixBias) + kFixOne;
 }
 
 __device__ __forceinline__ float from_fixed(unsigned long long total)
 {
-    const unsigned long long cnt = total >> 56;
-    const long long fx = (long long)(total & (kFixOne - 1)) - (long long)(cnt * kFixBias);
+    const unsigned long long cnt = total >> 58;
+    const long long fx = (long long)(total & (kFixPoison - 1)) - (long long)(cnt * kFixBias);
     return (float)((double)fx * (1.0 / 16777216.0));
+}
+
+// One slice's sum into the accumulator word of an output; the last of `split` arrivals casts, stores Y and
+// clears the word.  `nan` says the slice sum is NaN (`add` then carries the value 0).
+__device__ __forceinline__ void add_slice(unsigned long long *word, unsigned long long add, bool nan, int split, uint16_t *y)
+{
+    if (nan) __hip_atomic_fetch_or(word, kFixPoison, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ahead of this slice's add: same thread, same address
+    const unsigned long long total = __hip_atomic_fetch_add(word, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+    if ((total >> 58) == (unsigned long long)split) {
+        *y = (total & kFixPoison) ? kHalfNaN : (uint16_t)(pack_half2(from_fixed(total), 0.f) & 0xFFFFu);
+        __hip_atomic_store(word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // Sum of the waves' result tiles (ROWS x COLS each) in wave order, `red_waves` waves per round through
@@ -84,12 +110,9 @@ __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int f
             else
                 *reinterpret_cast<float4_t *>(a.partials + (size_t)slice * a.M * a.N + out) = v[k];
         } else {
-            const unsigned long long add = to_fixed(v[k][0]);
-            const unsigned long long total = __hip_atomic_fetch_add(sync + out, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
-            if ((total >> 56) == (unsigned long long)a.split) {
-                a.Y[out] = (uint16_t)(pack_half2(from_fixed(total), 0.f) & 0xFFFFu);
-                __hip_atomic_store(sync + out, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            const float sum = v[k][0];
+            const bool nan = sum != sum;
+            add_slice(sync + out, to_fixed(nan ? 0.f : sum), nan, a.split, a.Y + out);
         }
     }
 }

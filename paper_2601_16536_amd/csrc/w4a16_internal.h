@@ -32,12 +32,12 @@ enum Finish : int {
     kFinishSecondPass = 2    // FP32 partials [S, M, N], summed by the separate reduction kernel
 };
 
-// What a launch needs for its finish: S = 1 exactly when direct, the accumulator's count holds 255 slices.
+// What a launch needs for its finish: S = 1 exactly when direct, the accumulator's count holds 63 slices.
 inline bool finish_args_ok(const GemmArgs &a, int finish, const unsigned long long *sync)
 {
     switch (finish) {
     case kFinishDirect: return a.split == 1;
-    case kFinishAccumulator: return a.split > 1 && a.split <= 255 && sync;
+    case kFinishAccumulator: return a.split > 1 && a.split <= 63 && sync;
     case kFinishSecondPass: return a.split > 1 && a.partials;
     default: return false;
     }
@@ -51,6 +51,11 @@ size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves);  // 
 int stripe_lds_limit();                                                       // most it may use
 int stripe_min_waves(int M);
 int stripe_max_waves(int M);
+// STRIPE family for M <= 4: the slice is handed out to the waves in units of `unit_rows` packed rows (2 or 4) by an
+// LDS ticket counter, `depth` units in flight per wave; X, scales and zero points of the slice are staged in LDS.
+hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int unit_rows, int depth, hipStream_t stream);
+size_t stripe_dyn_lds_bytes(int M, int group, int groups_per_split);  // LDS one workgroup needs
+int stripe_dyn_lds_limit();                                           // most it may use
 // TILE family (the scheduler takes it for M >= 5): 64-column tiles, `rows_x` (16, 32 or 64) rows of X per
 // workgroup, `waves` (4..8) waves per workgroup that split the K slice; `finish` and `sync` as in the STRIPE
 // family.

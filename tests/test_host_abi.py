@@ -97,12 +97,19 @@ def test_plans_are_well_formed(binding, M, N, K):
             S, gps = p["split"], p["groups_per_split"]
             assert 1 <= S <= G
             assert S * gps >= G and (S - 1) * gps < G  # slices cover K, none empty
-            if split:
-                assert S <= split
             stripe = p["kernel"] == binding.KERNEL_STRIPE
+            if split and not (stripe and M <= 4):
+                assert S <= split
+            if split and stripe and M <= 4:
+                # the M <= 4 form stages the slice's X, scales and zero points in LDS (144 KiB): S is raised,
+                # by halving the slice, only where the forced slice would not fit
+                m = 1 if M == 1 else (2 if M == 2 else 4)
+                lds = lambda g: 32 + m * 2048 + g * (16 * 16 * m + 16 * 4 * m + 512 + 128)
+                assert S <= split or lds(-(-G // split)) > 144 * 1024
+                assert lds(gps) <= 144 * 1024
             # STRIPE and TILE slices meet in the 64-bit accumulator while the adds are few; else, and in
             # the other families, FP32 partials go to the second pass
-            in_acc = p["kernel"] in (binding.KERNEL_STRIPE, binding.KERNEL_TILE) and S <= 255 and S * M * N <= 640 * 1024
+            in_acc = p["kernel"] in (binding.KERNEL_STRIPE, binding.KERNEL_TILE) and S <= 63 and S * M * N <= 640 * 1024
             want = 0 if S == 1 else (M * N * 8 if in_acc else S * M * N * 4)
             assert p["workspace_bytes"] == want
             packed = 0.5 * K * N  # bytes of packed weights: the scheduler's STRIPE / TILE rule
@@ -119,6 +126,43 @@ def test_plans_are_well_formed(binding, M, N, K):
             else:
                 assert p["threads"] == 1024 and p["waves_k"] == 16
     assert binding.workspace_bytes(M, N, K, 128) >= binding.query_plan(M, N, K, 128)["workspace_bytes"]
+
+
+def test_shapes_beyond_32_bit_offsets_are_refused(binding):
+    """The kernels address X with 32-bit byte offsets: M K 2 >= 2^31 - 2^24 bytes answers W4A16_ERR_UNSUPPORTED
+    from every family, before anything touches a GPU."""
+    K = 1 << 26
+    for kernel, M in ((binding.KERNEL_AUTO, 16), (binding.KERNEL_STRIPE, 16), (binding.KERNEL_TILE, 16), (binding.KERNEL_TILE, 40),
+                      (binding.KERNEL_WAVE_SPLIT, 4), (binding.KERNEL_STRIPE, 4)):
+        big = M * K * 2 >= 0x7F000000
+        if big:
+            with pytest.raises(binding.W4A16Error) as e:
+                binding.query_plan(M, 64, K, 128, kernel=kernel)
+            assert e.value.status == binding.ERR_UNSUPPORTED
+            assert binding.raw_gemm_ex(16, 16, 16, 16, 128, M, 64, K, 16, 0, kernel, 0) in (binding.ERR_UNSUPPORTED, binding.ERR_HIP)
+        else:
+            assert binding.query_plan(M, 64, K, 128, kernel=kernel)["split"] >= 1
+    assert binding.query_plan(15, 64, K, 128, kernel=binding.KERNEL_STRIPE)["split"] >= 1  # 15 * 2^27 bytes still fits
+
+
+def test_tuning_knobs(binding):
+    """w4a16_tune changes the plans of later calls and rejects unknown names."""
+    assert binding.query_plan(40, 2048, 1024, 128, kernel=binding.KERNEL_TILE)["tile_m"] == 16
+    binding.tune("tile_rows", 64)
+    try:
+        assert binding.query_plan(40, 2048, 1024, 128, kernel=binding.KERNEL_TILE)["tile_m"] == 64
+    finally:
+        binding.tune("tile_rows", 0)
+    assert binding.query_plan(40, 2048, 1024, 128, kernel=binding.KERNEL_TILE)["tile_m"] == 16
+    with pytest.raises(binding.W4A16Error) as e:
+        binding.tune("no_such_knob", 1)
+    assert e.value.status == binding.ERR_UNSUPPORTED
+    assert binding.lib().w4a16_tune(None, 1) == binding.ERR_NULL
+
+
+def test_set_workspace_argument_checks(binding):
+    assert binding.lib().w4a16_set_workspace(128, 1 << 20) == binding.ERR_ALIGN
+    assert binding.lib().w4a16_set_workspace(256, 16) == binding.ERR_WORKSPACE
 
 
 def test_headline_plan_is_one_launch(binding):
