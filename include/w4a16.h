@@ -110,8 +110,8 @@ typedef struct {
  * already enqueued, or recorded in a HIP graph, keeps pointing at valid
  * memory).  While `stream` is being captured into a graph nothing can be
  * allocated: a call that would have to returns W4A16_ERR_WORKSPACE; run the
- * same shape once outside the capture first, or use w4a16_set_workspace or
- * w4a16_gemm_ws.  If a launch fails
+ * same shape once outside the capture first, or use w4a16_set_workspace,
+ * w4a16_gemm_ws or w4a16_gemm_noalloc.  If a launch fails
  * (W4A16_ERR_HIP) the library clears its accumulator again before the next use.
  */
 int w4a16_gemm(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
@@ -151,6 +151,21 @@ int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, co
  * initialisation.  Calls that overlap in time on one device share it and race.
  */
 int w4a16_set_workspace(void *workspace, size_t workspace_bytes);
+
+/*
+ * w4a16_gemm_ex for callers that cannot allocate device memory or wait for the device: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result as w4a16_gemm_ex
+ * (kernel = W4A16_KERNEL_AUTO and split = 0 give w4a16_gemm's plan).  The split buffers are a fixed array of
+ * W4A16_NOALLOC_SCRATCH_BYTES that the library's code object holds on every GPU it is loaded on until the
+ * process ends; the call allocates nothing, frees nothing and waits for nothing.  A plan that needs more returns
+ * W4A16_ERR_WORKSPACE and launches nothing (w4a16_query_plan tells what a plan needs; the scheduler's own plans
+ * stay below 1.1 MiB on a GPU of 256 compute units).  A plan that uses the array as accumulator clears that part with one small extra launch first (a
+ * kernel, so the call can be captured).  All such calls on one GPU share the one array: calls that overlap in
+ * time on that GPU (different streams, or graphs replayed concurrently) race on it.
+ */
+#define W4A16_NOALLOC_SCRATCH_BYTES (4u << 20)
+int w4a16_gemm_noalloc(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
+                       int group, int M, int N, int K, void *Y, void *stream, int kernel, int split);
 
 /* Bytes of split buffers (Section 3) that the plan the scheduler itself chooses for this shape needs (at least
  * 256); forced plans: w4a16_query_plan. */

@@ -16,7 +16,7 @@ ERR_NULL, ERR_SHAPE, ERR_GROUP, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORT
 KERNEL_AUTO, KERNEL_WAVE_SPLIT, KERNEL_STRIPE, KERNEL_TILE = -1, 0, 3, 4  # 1 and 2: retired families
 
 EXPORTS = (
-    "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_set_workspace", "w4a16_tune",
+    "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_gemm_noalloc", "w4a16_set_workspace", "w4a16_tune",
     "w4a16_workspace_bytes", "w4a16_query_plan",
     "w4a16_reduce", "w4a16_dequant", "w4a16_quantize", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
 )
@@ -64,6 +64,7 @@ def lib():
         L.w4a16_gemm.argtypes = gemm_args
         L.w4a16_gemm_ex.argtypes = gemm_args + [ci, ci]
         L.w4a16_gemm_ws.argtypes = gemm_args + [ci, ci, vp, sz]
+        L.w4a16_gemm_noalloc.argtypes = gemm_args + [ci, ci]
         L.w4a16_set_workspace.argtypes = [vp, sz]
         L.w4a16_tune.argtypes = [ctypes.c_char_p, ci]
         L.w4a16_workspace_bytes.argtypes = [ci, ci, ci, ci]
@@ -125,6 +126,23 @@ def raw_gemm_ex(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, k
 def raw_gemm_ws(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel, split, ws_ptr, ws_bytes) -> int:
     return lib().w4a16_gemm_ws(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel, split,
                                ws_ptr, ws_bytes)
+
+
+def raw_gemm_noalloc(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel=KERNEL_AUTO, split=0) -> int:
+    """w4a16_gemm_noalloc on raw device addresses; returns the status code."""
+    return lib().w4a16_gemm_noalloc(X_ptr, W_ptr, s_ptr, z_ptr, group, M, N, K, Y_ptr, stream_ptr, kernel, split)
+
+
+def gemm_noalloc(X, Wpacked, scales, zeros, group: int, out, kernel: int = KERNEL_AUTO, split: int = 0, stream=None):
+    """As gemm_ex, through the entry point that allocates nothing: the caller brings Y as well."""
+    M, N, K = _check_tensors(X, Wpacked, scales, zeros, group)
+    if tuple(out.shape) != (M, N) or not out.is_contiguous():
+        raise ValueError("out must be a contiguous [M, N] tensor")
+    rc = raw_gemm_noalloc(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, M, N, K,
+                          out.data_ptr(), _stream(stream), kernel, split)
+    if rc:
+        raise W4A16Error(rc, "w4a16_gemm_noalloc")
+    return out
 
 
 def set_workspace(workspace) -> None:

@@ -17,6 +17,12 @@ using namespace w4a16;
 
 constexpr int kMaxDevices = 64;
 
+// Split buffers for callers that cannot allocate (w4a16_gemm_noalloc): one array per GPU the library is loaded on,
+// held until the process ends.  Host code never uses the array's name as an address: each device's copy is
+// looked up once with hipGetSymbolAddress.
+constexpr size_t kScratchBytes = W4A16_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 struct DeviceState {
     int cus = 0;             // compute units (0 = not read yet)
     void *ws = nullptr;      // library-owned workspace (fp32 partials of the two-pass plans)
@@ -27,6 +33,7 @@ struct DeviceState {
     std::vector<void *> retired;  // outgrown buffers: work already enqueued (or captured in a graph) may still use them
     void *user_ws = nullptr;      // w4a16_set_workspace: the caller's split buffers for this device
     size_t user_ws_bytes = 0;
+    void *scratch_ptr = nullptr;  // this device's copy of `scratch`
 };
 
 std::mutex g_mutex;
@@ -330,7 +337,7 @@ int grow(DeviceState &d, void **buf, size_t *have, size_t bytes, size_t floor_by
     return W4A16_OK;
 }
 
-enum Source { kFromLibrary, kFromCall };
+enum Source { kFromLibrary, kFromCall, kFromScratch };
 
 struct Buffers {
     unsigned long long *sync = nullptr;  // the accumulator: zero before the launch, left zero by it
@@ -347,6 +354,17 @@ int find_buffers(int dev, const w4a16_plan &plan, int finish, int M, int N, hipS
     if (src == kFromCall) {
         given = call_ws;
         given_bytes = call_ws_bytes;
+    } else if (src == kFromScratch) {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        DeviceState &d = g_dev[dev];
+        if (!d.scratch_ptr) {  // once per device, with that device current
+            void *ptr = nullptr;
+            hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) { note_hip_error(e); (void)hipGetLastError(); return W4A16_ERR_HIP; }
+            d.scratch_ptr = ptr;
+        }
+        given = d.scratch_ptr;
+        given_bytes = kScratchBytes;
     } else {
         std::lock_guard<std::mutex> lock(g_mutex);
         if (g_dev[dev].user_ws) {
@@ -480,6 +498,12 @@ int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, co
                   int N, int K, void *Y, void *stream, int kernel, int split, void *workspace, size_t workspace_bytes)
 {
     return run("gemm_ws", X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, kFromCall, workspace, workspace_bytes);
+}
+
+int w4a16_gemm_noalloc(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int M,
+                       int N, int K, void *Y, void *stream, int kernel, int split)
+{
+    return run("gemm_noalloc", X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, kFromScratch, nullptr, 0);
 }
 
 int w4a16_set_workspace(void *workspace, size_t workspace_bytes)
