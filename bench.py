@@ -56,9 +56,10 @@ def log(*a):
 
 
 def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, warm=False, host=None, graph=True,
-              replays=3):
+              replays=5):
     """Returns dict with µs per GEMM: HIP events around `steps` back-to-back GEMMs (one replay of a HIP graph
-    that holds them, best of `replays`; graph=False times the eager Python loop instead)."""
+    that holds them; the median of `replays` replays is the value, the fastest is reported beside it;
+    graph=False times the eager Python loop instead)."""
     cfg = wl.config(name)
     if host is None:
         host = wl.make_config(name)
@@ -89,27 +90,26 @@ def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, wa
                 call(warmup + i)
         g.replay()  # untimed: first replay of a new graph
         torch.cuda.synchronize()
-        best = None
+        times = []
         for _ in range(replays):
             e0.record(stream)
             g.replay()
             e1.record(stream)
             torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1)
-            best = ms if best is None else min(best, ms)
-        us = best * 1e3 / steps
+            times.append(e0.elapsed_time(e1) * 1e3 / steps)
+        us, us_min = float(np.median(times)), min(times)
     else:
         e0.record(stream)
         for i in range(steps):
             call(warmup + i)
         e1.record(stream)
         torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / steps
+        us = us_min = e0.elapsed_time(e1) * 1e3 / steps
     nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, cfg.group)
     flops = 2.0 * M * cfg.K * cfg.N
     plan = binding.query_plan(M, cfg.N, cfg.K, cfg.group, kernel, split)
     res = {
-        "config": name, "M": M, "K": cfg.K, "N": cfg.N, "us_per_gemm": us,
+        "config": name, "M": M, "K": cfg.K, "N": cfg.N, "us_per_gemm": us, "us_per_gemm_min": us_min,
         "algorithmic_bytes": nbytes, "GBps": nbytes / us * 1e-3, "hbm_frac": nbytes / us * 1e-3 / HBM_PEAK_GBS,
         "TFLOPs": flops / us * 1e-6, "mfma_frac": flops / us * 1e-6 / MFMA_FP16_PEAK_TFLOPS,
         "cache": "warm (one weight copy, last-level-cache resident)" if warm else "cold (%d weight copies)" % copies,
@@ -305,6 +305,7 @@ def main():
         "config": {"workload": "%s: M=%d K=%d N=%d group=%d, W4A16, %s" % (args.config, args.M, cfg.K, cfg.N,
                                                                           cfg.group, res["cache"]),
                    "plan": res["plan"]},
+        "us_per_gemm_min": res["us_per_gemm_min"], "timing": "median of 5 replays of a HIP graph of %d GEMMs (fastest replay beside it)" % args.steps,
         "achieved_TBps": res["GBps"] * 1e-3, "achieved_TFLOPs": res["TFLOPs"],
         # the roofline that bounds the kernel: HBM below the ridge of 2.5 PFLOP/s over 8 TB/s = 312.5 flop/byte, MFMA above
         "roofline": ({"bound": "hbm", "achieved": res["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["hbm_frac"]}
@@ -316,6 +317,7 @@ def main():
                      "launches_per_step": 1 if res["plan"]["split"] == 1 or res["plan"]["workspace_bytes"] ==
                      8 * args.M * cfg.N else 2,
                      "kernel": ("tile_group_kernel" if res["plan"]["kernel"] == 4 and cfg.group == 128 else
+                                "stripe_dyn_kernel" if res["plan"]["kernel"] == 3 and args.M <= 4 else
                                 KERNEL_NAMES.get(res["plan"]["kernel"], "?")),
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"],
                      "algorithmic_flops_per_launch": 2.0 * args.M * cfg.K * cfg.N})

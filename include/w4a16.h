@@ -75,11 +75,10 @@ typedef enum {
     W4A16_KERNEL_AUTO = -1,
     W4A16_KERNEL_WAVE_SPLIT = 0, /* M <= 4: narrow column tile per workgroup, its 16 waves split K, LDS reduction */
     /* 1 and 2 belonged to two earlier families, retired: W4A16_ERR_UNSUPPORTED */
-    W4A16_KERNEL_STRIPE = 3,     /* M <= 16; the scheduler's choice for M <= 2 (M <= 4) from about 10 MB (48 MB) of
-                                    packed weights on: 256-column stripe x K slice per workgroup, its waves own
-                                    contiguous runs of the slice (LDS reduction); slices of different workgroups
-                                    meet in a 64-bit fixed-point accumulator by one atomic add each, no second
-                                    launch                                                                        */
+    W4A16_KERNEL_STRIPE = 3,     /* M <= 16; the scheduler's choice for M = 1 (2; 3, 4) from about 4 MB (20 MB; 32 MB)
+                                    of packed weights on: 256-column stripe x K slice per workgroup, its waves
+                                    share the slice (exact sums in LDS); slices of different workgroups meet in a
+                                    64-bit fixed-point accumulator by one atomic add each, no second launch        */
     W4A16_KERNEL_TILE = 4        /* any M, the scheduler's choice otherwise: 64-column tile x 16, 32 or 64 rows of X
                                     per workgroup, its waves own contiguous runs of K (LDS reduction), plain MFMA
                                     operand layout; slices of different workgroups meet as in STRIPE                */
@@ -203,8 +202,8 @@ int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, 
  *   "stripe_finish"  1: K slices of different workgroups always meet in the accumulator, 2: always second pass
  *   "stripe_waves"   waves per STRIPE workgroup
  *   "stripe_dyn"     M <= 4: 2 = equal contiguous runs per wave instead of units handed out by ticket
- *   "stripe_unit"    packed rows per unit handed out (2 or 4)
- *   "stripe_depth"   units in flight per wave (1..4)
+ *   "stripe_unit"    packed rows per unit handed out (2, 4 or 8)
+ *   "stripe_depth"   units in flight per wave (1..4; 9 = one, its successor requested ahead of its use)
  *   "tile_rows"      rows of X per TILE workgroup (16, 32, 64)
  *   "tile_waves"     waves per TILE workgroup (4..8)
  *   "log"            1: every w4a16_gemm* call prints its plan on stderr (the one case in which the library prints)

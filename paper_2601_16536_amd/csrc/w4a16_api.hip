@@ -138,7 +138,7 @@ bool fits_32bit_offsets(int M, int N, int K, int group, int gps)
 // Algorithm 1 takes the split factor S and the block sizes as inputs.  Here the
 // scheduler (kernel = AUTO, split = 0) chooses them from the shape alone:
 //
-// STRIPE (M <= 2 from about 10 MB of packed weights on, M <= 4 from about 48 MB on): 256-column stripes
+// STRIPE (M = 1 from about 4 MB of packed weights on, M = 2 from about 20 MB, M <= 4 from about 32 MB): 256-column stripes
 //   x S slices of K with S = compute units / stripes, rounded down: one workgroup per compute unit whose
 //   waves share the slice.
 // TILE (everything else): 64-column tiles x 16, 32 or 64 rows of X per workgroup (as many rows as still
@@ -194,11 +194,12 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
     const int G = K / group;
     if (kernel == W4A16_KERNEL_AUTO) {
         // STRIPE streams large weight matrices faster than TILE, but its 256-column stripes need four
-        // times the slices, hence four times the atomic adds (S M N), and it carries more fixed cost.
-        // Measured on sixteen shapes from 2 MB to 117 MB of packed weights: STRIPE wins for M <= 2 from about
-        // 10 MB on, for M = 3, 4 only from about 48 MB on; TILE everywhere else.
+        // times the slices, hence four times the atomic adds (S M N), and its work per unit of K grows with M.
+        // Measured on the five configurations, the six (N, K) pairs of the paper's Fig. 2 and three K << N shapes
+        // (2 MB to 117 MB of packed weights): STRIPE wins at M = 1 from about 4 MB on, at M = 2 from about
+        // 20 MB on, at M = 3, 4 from about 32 MB on; TILE everywhere else.
         const double packed = 0.5 * (double)K * (double)N;
-        const bool stripe = (M <= 2 && packed >= 10e6) || (M <= 4 && packed >= 48e6);
+        const bool stripe = (M == 1 && packed >= 4e6) || (M == 2 && packed >= 20e6) || (M <= 4 && packed >= 32e6);
         kernel = stripe ? W4A16_KERNEL_STRIPE : W4A16_KERNEL_TILE;
     }
     if (kernel != W4A16_KERNEL_WAVE_SPLIT && kernel != W4A16_KERNEL_STRIPE && kernel != W4A16_KERNEL_TILE)
@@ -226,11 +227,11 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         S = (G + gps - 1) / gps;
         if (stripe_lds(M, group, gps, wmin) > stripe_lds_max(M)) return W4A16_ERR_UNSUPPORTED;
         if (S > 65535) return W4A16_ERR_UNSUPPORTED;  // a grid dimension of the many-row form
-        // waves: each should own at least four blocks of 16 k; twelve measured best on the large shapes for
-        // M <= 4 (ten to sixteen are within 3 % of each other); the many-row form holds eight at most
+        // waves: each should get at least four blocks of 16 k; eight measured best for the ticket form (M <= 4), which
+        // is also the most the many-row form holds
         const long long nblocks = (long long)gps * (group / 16);
         int waves = (int)(nblocks / 4);
-        const int wbest = wmax > 12 ? 12 : wmax;
+        const int wbest = stripe_by_ticket(M) ? 8 : (wmax > 12 ? 12 : wmax);
         waves = waves < wmin ? wmin : (waves > wbest ? wbest : waves);
         if (tuning().stripe_waves >= wmin && tuning().stripe_waves <= wmax) waves = tuning().stripe_waves;
         while (waves > wmin && stripe_lds(M, group, gps, waves) > stripe_lds_max(M)) --waves;
@@ -457,7 +458,10 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
 
     hipError_t e;
     if (plan.kernel == W4A16_KERNEL_STRIPE && stripe_by_ticket(M)) {
-        const int unit = tuning().stripe_unit == 4 ? 4 : 2, depth = tuning().stripe_depth >= 1 && tuning().stripe_depth <= 4 ? tuning().stripe_depth : 2;
+        // measured on K = 4096 ... 28672 at M = 1, 2, 4: units of four packed rows, one in flight per wave, eight waves
+        // (deeper rings, smaller or larger units, a successor requested ahead of use: all slower by 2 to 10 %)
+        const int tu = tuning().stripe_unit, td = tuning().stripe_depth;
+        const int unit = tu == 2 ? 2 : (tu == 8 && group % 64 == 0 ? 8 : 4), depth = td >= 1 && td <= 4 ? td : (td == 9 ? 0 : 1);
         e = launch_stripe_dyn(a, finish, b.sync, plan.waves_k, unit, depth, st);
     } else if (plan.kernel == W4A16_KERNEL_STRIPE) {
         e = launch_stripe(a, finish, b.sync, plan.waves_k, st);

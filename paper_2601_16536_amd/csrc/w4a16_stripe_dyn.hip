@@ -49,8 +49,7 @@ namespace {
 constexpr int kStripe = 256;            // columns per workgroup: 64 lanes x 4 words
 constexpr int kLdsLimit = 144 * 1024;
 constexpr float kFix48 = 281474976710656.0f;   // 2^48: P carries 2^-24, the sums are kept in units of 2^-24
-constexpr float kUnitMax = 562949953421312.0f;  // 2^49 = 2^25 in units of 2^-24: the clamp of one unit's contribution
-constexpr double kSumMax = 562949953421312.0;   // and of a wave's and a workgroup's sum
+constexpr double kSumMax = 562949953421312.0;   // 2^49 = 2^25 in units of 2^-24: the clamp of a wave's and a workgroup's sum
 constexpr long long kNaNMark = 1ll << 58;       // added to the LDS sum of an output by a wave whose sum is NaN
 
 // LDS of a workgroup, in this order (all 16-byte aligned):
@@ -76,7 +75,9 @@ __host__ __device__ inline Lds lds_layout(int mrows, int rows, int groups)
     return l;
 }
 
-template <int MROWS, int U, int D>
+// D units in flight per wave, a unit's successor requested when the unit has been used; or, AHEAD (D = 2 buffers):
+// one unit in flight, its successor requested just before the unit is used, so that a wave always has a request out.
+template <int MROWS, int U, int D, bool AHEAD>
 __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -166,8 +167,9 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
         for (int t = 0; t < U; ++t)
             b[t] = __builtin_amdgcn_raw_buffer_load_b128(rw, valid ? vw : kOutOfRange, valid ? (uint32_t)(row + t) * row_w : 0u, 2);  // read once: nontemporal
     };
+    constexpr int kStatic = AHEAD ? 1 : D;  // units per wave handed out without a ticket
 #pragma unroll
-    for (int p = 0; p < D; ++p) {
+    for (int p = 0; p < kStatic; ++p) {
         const int u = wave + p * waves;
         urow[p] = u < units ? u * U : -1;
         load_unit(buf[p], urow[p]);
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
     // ---- LDS set-up ----
     if (tid == 0) {
         *reinterpret_cast<uint4_t *>(smem) = (uint4_t){0u, 0u, 0u, 0u};
-        tickets[0] = (uint32_t)(waves * D);
+        tickets[0] = (uint32_t)(waves * kStatic);
     }
     for (int e = tid; e < MROWS * kStripe; e += nthreads) reinterpret_cast<unsigned long long *>(smem + L.acc)[e] = 0ull;
 #pragma unroll
@@ -247,30 +249,48 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
 #pragma unroll
             for (int i = 0; i < MROWS; ++i) {
                 float v = __builtin_fmaf(sp, part[c][i], sz24 * xs[i]);            // the unit's contribution, in units of 2^-24
-                v = __builtin_rintf(v);
-                v = v > kUnitMax ? kUnitMax : (v < -kUnitMax ? -kUnitMax : v);     // (a NaN stays one)
-                tot[c][i] += (double)v;                                            // exact: integers, the sum below 2^53
+                // exact from here on: integers, the sum below 2^53 unless the values are beyond 2^28, far outside
+                // the range the final clamp keeps anyway (an infinity or a NaN stays one)
+                tot[c][i] += (double)__builtin_rintf(v);
             }
         }
     };
 
-    for (;;) {
-        bool any = false;
-#pragma unroll
-        for (int p = 0; p < D; ++p) {
-            const int row = urow[p];
-            if (row >= 0) {
-                any = true;
+    if constexpr (AHEAD) {
+        static_assert(!AHEAD || D == 2, "two buffers");
+        int row = urow[0];
+        auto step = [&](uint4_t(&cur)[U], uint4_t(&nxt)[U]) -> bool {  // uses `cur`, requests its successor into `nxt` first
+            if (row < 0) return false;
+            const int rown = next < units ? next * U : -1;
+            load_unit(nxt, rown);
+            if (next < units) next = draw();
 #ifdef W4A16_TIMELINE
-                if (TF == 0) { asm volatile("" ::"v"(buf[p][0][0])); TF = __builtin_amdgcn_s_memrealtime(); }
+            if (TF == 0) { asm volatile("" ::"v"(cur[0][0])); TF = __builtin_amdgcn_s_memrealtime(); }
 #endif
-                compute_unit(buf[p], row);
-                urow[p] = next < units ? next * U : -1;
-                load_unit(buf[p], urow[p]);
-                if (next < units) next = draw();
+            compute_unit(cur, row);
+            row = rown;
+            return true;
+        };
+        while (step(buf[0], buf[1]) && step(buf[1], buf[0])) {}
+    } else {
+        for (;;) {
+            bool any = false;
+#pragma unroll
+            for (int p = 0; p < D; ++p) {
+                const int row = urow[p];
+                if (row >= 0) {
+                    any = true;
+#ifdef W4A16_TIMELINE
+                    if (TF == 0) { asm volatile("" ::"v"(buf[p][0][0])); TF = __builtin_amdgcn_s_memrealtime(); }
+#endif
+                    compute_unit(buf[p], row);
+                    urow[p] = next < units ? next * U : -1;
+                    load_unit(buf[p], urow[p]);
+                    if (next < units) next = draw();
+                }
             }
+            if (!any) break;
         }
-        if (!any) break;
     }
 #ifdef W4A16_TIMELINE
     const unsigned long long T1 = __builtin_amdgcn_s_memrealtime();
@@ -326,18 +346,18 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
 
 int mrows_of(int M) { return M == 1 ? 1 : (M == 2 ? 2 : 4); }
 
-template <int MROWS, int U, int D>
+template <int MROWS, int U, int D, bool AHEAD>
 hipError_t launch_m(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
 {
     const size_t lds = stripe_dyn_lds_bytes(a.M, a.group, a.groups_per_split);
     if (lds > (size_t)kLdsLimit) return hipErrorInvalidValue;
     const int nstripes = (a.N + kStripe - 1) / kStripe;
     if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_dyn_kernel<MROWS, U, D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_dyn_kernel<MROWS, U, D, AHEAD>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((stripe_dyn_kernel<MROWS, U, D>), dim3(a.split, nstripes), dim3(waves * 64), lds, stream, a, finish, sync);
+    hipLaunchKernelGGL((stripe_dyn_kernel<MROWS, U, D, AHEAD>), dim3(a.split, nstripes), dim3(waves * 64), lds, stream, a, finish, sync);
     return hipGetLastError();
 }
 
@@ -354,13 +374,15 @@ int stripe_dyn_lds_limit() { return kLdsLimit; }
 hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int unit_rows, int depth, hipStream_t stream)
 {
     if (a.M > 4 || a.group % 32 != 0 || waves < 1 || waves > 16) return hipErrorInvalidValue;
+    if ((a.group / 8) % unit_rows != 0) return hipErrorInvalidValue;  // a unit never crosses a quantisation group
     if (!finish_args_ok(a, finish, sync)) return hipErrorInvalidValue;
     const unsigned long long rows = (unsigned long long)a.groups_per_split * (a.group / 8);
     if (rows * a.N * 4ull >= 0x7F000000ull) return hipErrorInvalidValue;        // slice-relative 32-bit buffer offsets
     if ((unsigned long long)a.M * a.K * 2ull >= 0x7F000000ull) return hipErrorInvalidValue;
     if ((a.N + kStripe - 1) / kStripe > 65535) return hipErrorInvalidValue;  // stripes are the grid's y
+    // depth 0 = one unit in flight, its successor requested ahead of its use
 #define W4A16_DYN_CASE(MR, UU, DD) \
-    if (mrows_of(a.M) == MR && unit_rows == UU && depth == DD) return launch_m<MR, UU, DD>(a, finish, sync, waves, stream);
+    if (mrows_of(a.M) == MR && unit_rows == UU && depth == DD) return launch_m<MR, UU, (DD ? DD : 2), DD == 0>(a, finish, sync, waves, stream);
 #define W4A16_DYN_M(UU, DD) W4A16_DYN_CASE(1, UU, DD) W4A16_DYN_CASE(2, UU, DD) W4A16_DYN_CASE(4, UU, DD)
     W4A16_DYN_M(4, 2)
     W4A16_DYN_M(2, 2)
@@ -368,6 +390,10 @@ hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *
     W4A16_DYN_M(2, 3)
     W4A16_DYN_M(4, 3)
     W4A16_DYN_M(2, 4)
+    W4A16_DYN_M(8, 1)
+    W4A16_DYN_M(4, 0)
+    W4A16_DYN_M(2, 0)
+    W4A16_DYN_M(2, 1)
 #undef W4A16_DYN_M
 #undef W4A16_DYN_CASE
     return hipErrorInvalidValue;

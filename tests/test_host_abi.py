@@ -113,7 +113,7 @@ def test_plans_are_well_formed(binding, M, N, K):
             want = 0 if S == 1 else (M * N * 8 if in_acc else S * M * N * 4)
             assert p["workspace_bytes"] == want
             packed = 0.5 * K * N  # bytes of packed weights: the scheduler's STRIPE / TILE rule
-            auto = 3 if (M <= 2 and packed >= 10e6) or (M <= 4 and packed >= 48e6) else 4
+            auto = 3 if (M == 1 and packed >= 4e6) or (M == 2 and packed >= 20e6) or (M <= 4 and packed >= 32e6) else 4
             assert p["kernel"] == (kernel if kernel != binding.KERNEL_AUTO else auto)
             tiles_n = -(-N // p["tile_n"])
             tiles_m = -(-M // p["tile_m"]) if p["kernel"] not in (binding.KERNEL_WAVE_SPLIT, binding.KERNEL_STRIPE) else 1
