@@ -170,6 +170,52 @@ int w4a16_oracle_gemm_columns(const uint16_t *X, const uint32_t *Wp,
     return 0;
 }
 
+/* ---- variants the paper names without evaluating them ---------------------- */
+
+/* Symmetric quantization (Section 2.1: "symmetric" means z = 0 in Eq. 1, on
+ * signed codes).  Reading for this library's unsigned storage: the stored
+ * code is the signed code plus 8, so Dequant(W)[k,n] = s (q - 8) and there is
+ * no zero-point tensor.  Binary32, exact for the same reason as weight_at. */
+static inline float symmetric_weight_at(const uint32_t *Wp, const uint16_t *scales,
+                                        int group, int N, int k, int n)
+{
+    int grp = k / group;
+    int signed_code = code_at(Wp, N, k, n) - 8;   /* -8 .. 7 */
+    float s = w4a16_oracle_half_to_float(scales[(size_t)grp * (size_t)N + (size_t)n]);
+    return s * (float)signed_code;
+}
+
+/* w[K,N] (binary32) <- s (W - 8). */
+int w4a16_oracle_dequant_symmetric(const uint32_t *Wp, const uint16_t *scales,
+                                   int group, int K, int N, float *w)
+{
+    if (!shape_ok(group, 0, N, K)) return 1;
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n)
+            w[(size_t)k * N + n] = symmetric_weight_at(Wp, scales, group, N, k, n);
+    return 0;
+}
+
+/* ref[M,N] (binary64) <- A * s (W - 8): Eq. 2 with the symmetric reading,
+ * every product and sum in binary64, k ascending. */
+int w4a16_oracle_gemm_symmetric(const uint16_t *X, const uint32_t *Wp,
+                                const uint16_t *scales, int group,
+                                int M, int N, int K, double *ref)
+{
+    if (!shape_ok(group, M, N, K)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            double sum = 0.0;
+            for (int k = 0; k < K; ++k) {
+                double x = (double)w4a16_oracle_half_to_float(X[(size_t)m * K + k]);
+                sum += x * (double)symmetric_weight_at(Wp, scales, group, N, k, n);
+            }
+            ref[(size_t)m * N + n] = sum;
+        }
+    return 0;
+}
+
 /* Threads the gemm above spreads its columns over. */
 int w4a16_oracle_threads(void)
 {

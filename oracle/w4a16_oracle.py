@@ -53,6 +53,8 @@ def _load():
         lib.w4a16_oracle_dequant.argtypes = [u32p, u16p, u32p, ci, ci, ci, f32p]
         lib.w4a16_oracle_gemm.argtypes = [u16p, u32p, u16p, u32p, ci, ci, ci, ci, f64p]
         lib.w4a16_oracle_gemm_columns.argtypes = [u16p, u32p, u16p, u32p, ci, ci, ci, ci, i32p, ci, f64p]
+        lib.w4a16_oracle_dequant_symmetric.argtypes = [u32p, u16p, ci, ci, ci, f32p]
+        lib.w4a16_oracle_gemm_symmetric.argtypes = [u16p, u32p, u16p, ci, ci, ci, ci, f64p]
         lib.w4a16_oracle_threads.argtypes = []
         _lib = lib
     return _lib
@@ -151,6 +153,38 @@ def gemm(X, Wp, scales, Zp, group: int, cols=None) -> np.ndarray:
             _ptr(Zp, ctypes.c_uint32), group, M, N, K, _ptr(cols, ctypes.c_int32), int(cols.size),
             _ptr(ref, ctypes.c_double))
     if rc:
+        raise ValueError("oracle rejected the arguments")
+    return ref
+
+
+def _check_symmetric(Wp, scales, group):
+    Wp, s = _u32(Wp), _u16(scales)
+    R, N = Wp.shape
+    K = R * 8
+    if group < 1 or K % group or N % 8 or s.shape != (K // group, N):
+        raise ValueError("scales %r do not fit K=%d N=%d group=%d" % (s.shape, K, N, group))
+    return Wp, s, K, N
+
+
+def dequant_symmetric(Wp, scales, group: int) -> np.ndarray:
+    """Symmetric reading of Section 2.1 (z = 0 on signed codes = stored code - 8): s (W - 8) as binary32 [K, N]."""
+    Wp, s, K, N = _check_symmetric(Wp, scales, group)
+    w = np.empty((K, N), np.float32)
+    if _load().w4a16_oracle_dequant_symmetric(_ptr(Wp, ctypes.c_uint32), _ptr(s, ctypes.c_uint16), group, K, N,
+                                              _ptr(w, ctypes.c_float)):
+        raise ValueError("oracle rejected the shape")
+    return w
+
+
+def gemm_symmetric(X, Wp, scales, group: int) -> np.ndarray:
+    """ref = A * s (W - 8) in binary64 [M, N]: Eq. 2 without a zero-point tensor."""
+    Wp, s, K, N = _check_symmetric(Wp, scales, group)
+    X = _u16(X)
+    if X.ndim != 2 or X.shape[1] != K:
+        raise ValueError("X %r does not fit K=%d" % (X.shape, K))
+    ref = np.empty((X.shape[0], N), np.float64)
+    if _load().w4a16_oracle_gemm_symmetric(_ptr(X, ctypes.c_uint16), _ptr(Wp, ctypes.c_uint32), _ptr(s, ctypes.c_uint16),
+                                           group, X.shape[0], N, K, _ptr(ref, ctypes.c_double)):
         raise ValueError("oracle rejected the arguments")
     return ref
 
