@@ -3,6 +3,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
                     [--config c4] [--M 1] [--kernel -1] [--split 0] [--warm] [--table] [--fig2] [--ablation]
+                    [--split-sweep] [--timeline]
 
 A step is one whole GEMM (Eq. 2: every launch w4a16_gemm enqueues for it) on
 seeded synthetic inputs already resident in HBM.  By default consecutive steps
@@ -183,6 +184,76 @@ def fig2(torch, binding, wl, max_steps):
     return rows
 
 
+def split_sweep(torch, binding, wl, max_steps):
+    """The evidence behind the scheduler's split factors (Algorithm 1 takes S as an input and gives no rule):
+    us per GEMM against S for both families the scheduler uses, cold weights, on the decode configurations
+    and the (N, K) pairs of the paper's Fig. 2."""
+    rows = []
+    cases = [("c2", (1,)), ("c3", (1, 4, 16)), ("c4", (1, 8)), ("f2a", (1, 16)), ("f2b", (1, 16)), ("f2c", (1, 16)),
+             ("f2d", (1, 16)), ("f2e", (1, 16)), ("f2f", (1, 16))]
+    for name, Ms in cases:
+        c = wl.config(name)
+        h = wl.make_config(name)
+        G = c.K // c.group
+        steps = max(50, min(max_steps, int(1e5 / max(1.0, 1e-6 * c.K * c.N / 16))))
+        for M in Ms:
+            auto = binding.query_plan(M, c.N, c.K, c.group)
+            for fam, kid in (("stripe", binding.KERNEL_STRIPE), ("tile", binding.KERNEL_TILE)):
+                if kid == binding.KERNEL_STRIPE and M > 16:
+                    continue
+                own = binding.query_plan(M, c.N, c.K, c.group, kid, 0)["split"]
+                tried = {}
+                for S in sorted({1, 2, 3, 4, 6, 7, 8, 12, 14, 16, 24, 28, 32, 48, 56, own}):
+                    if S > G:
+                        continue
+                    plan = binding.query_plan(M, c.N, c.K, c.group, kid, S)
+                    if plan["split"] in tried:
+                        continue
+                    r, _, _ = time_gemm(torch, binding, wl, name, M, steps, 10, kernel=kid, split=S, host=h, replays=3)
+                    tried[plan["split"]] = r["us_per_gemm"]
+                best = min(tried, key=tried.get)
+                row = {"shape": name, "N": c.N, "K": c.K, "M": M, "family": fam, "us_by_split": tried,
+                       "family_choice": own, "family_choice_us": tried[own], "best_split": best, "best_us": tried[best],
+                       "scheduler_takes_this_family": auto["kernel"] == kid}
+                log(json.dumps(row))
+                rows.append(row)
+        del h
+    return rows
+
+
+def timeline(torch, binding, wl, name, M):
+    """Per-phase time stamps of the decode kernel (profiling build of the library, M <= 4 stripe plans): one
+    eager launch on cold weights after a few warm-up launches."""
+    import ctypes
+    cfg = wl.config(name)
+    host = wl.make_config(name)
+    Xall, Wp, s, Zp = host
+    X = np.ascontiguousarray(Xall[:M])
+    plan = binding.query_plan(M, cfg.N, cfg.K, cfg.group)
+    if plan["kernel"] != binding.KERNEL_STRIPE or M > 4:
+        sys.exit("bench.py --timeline: the scheduler's plan for this shape is not the decode kernel")
+    base = binding.to_device(X, Wp, s, Zp)
+    wbytes = Wp.nbytes + s.nbytes + Zp.nbytes
+    copies = max(2, -(-COLD_BYTES // wbytes))
+    sets = [base[1:]] + [tuple(t.clone() for t in base[1:]) for _ in range(copies - 1)]
+    waves, wgs = plan["waves_k"], plan["workgroups"]
+    words = torch.zeros(wgs * 16 * 8, dtype=torch.int64, device="cuda")
+    setter = binding.lib().w4a16_timeline_buffer
+    setter.argtypes = [ctypes.c_void_p]
+    assert setter(words.data_ptr()) == 0
+    for i in range(2 * copies + 1):
+        binding.gemm(base[0], *sets[i % copies], cfg.group)
+    torch.cuda.synchronize()
+    setter(None)
+    t = words.cpu().numpy().reshape(wgs, 16, 8)[:, :waves, :].astype(np.float64)
+    t0 = t[:, :, 0].min()
+    us = lambda col: (t[:, :, col] - t0) / 100.0
+    phases = {"kernel_entry_last_wave": us(0).max(), "first_unit_in_use_mean": us(1).mean(), "first_unit_in_use_last_wave": us(1).max(),
+              "loop_end_first_wave": us(2).min(), "loop_end_mean": us(2).mean(), "loop_end_last_wave": us(2).max(),
+              "workgroup_sums_done_last": us(3).max(), "atomic_add_back_last": us(4).max(), "exit_last_wave": us(5).max()}
+    return {"config": name, "M": M, "plan": plan, "us_after_first_wave_entry": {k: round(float(v), 2) for k, v in phases.items()}}
+
+
 def time_calls(torch, fn, steps, warmup, replays=3):
     """us per call of fn(i): HIP events around one replay of a HIP graph holding `steps` calls; the eager
     loop where the calls cannot be captured."""
@@ -267,6 +338,10 @@ def main():
     ap.add_argument("--ablation", action="store_true",
                     help="also time the unfused variant (dequantised FP16 weights through HBM + vendor FP16 GEMM) "
                          "and the FP16 x FP16 GEMM alone against the fused path (Section 4.2)")
+    ap.add_argument("--split-sweep", action="store_true", help="also time every admissible split factor S of both families "
+                    "on the decode shapes (the evidence behind the scheduler's choices)")
+    ap.add_argument("--timeline", action="store_true", help="print the decode kernel's per-phase time stamps for --config / --M "
+                    "from the profiling build (python -m paper_2601_16536_amd.build --timeline) and exit")
     ap.add_argument("--out", default=None, help="directory for bench_table.json, bench_fig2.json, bench_ablation.json")
     ap.add_argument("--no-cpu", action="store_true", help="skip the host-baseline leg")
     args = ap.parse_args()
@@ -278,10 +353,18 @@ def main():
     from paper_2601_16536_amd import binding, workloads as wl
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.timeline:
+        from paper_2601_16536_amd import build as hip_build
+        if not os.path.exists(hip_build.TIMELINE_LIB):
+            sys.exit("bench.py --timeline: build the profiling library first (python -m paper_2601_16536_amd.build --timeline)")
+        binding.use_library(hip_build.TIMELINE_LIB)
     binding.lib()
     torch.cuda.set_device(0)
+    if args.timeline:
+        print(json.dumps(timeline(torch, binding, wl, args.config, args.M)), flush=True)
+        return
 
-    cfg = wl.CONFIGS[args.config]
+    cfg = wl.config(args.config)
     host = wl.make_config(args.config)
     res, Y, _ = time_gemm(torch, binding, wl, args.config, args.M, args.steps, args.warmup, args.kernel, args.split,
                           args.warm, host)
@@ -340,6 +423,9 @@ def main():
     if args.ablation:
         line["ablation"] = ablation(torch, binding, wl, args.steps)
         save(args.out, "bench_ablation.json", line["ablation"])
+    if args.split_sweep:
+        line["split_sweep"] = split_sweep(torch, binding, wl, args.steps)
+        save(args.out, "bench_split_sweep.json", line["split_sweep"])
     if args.fig2:
         line["fig2"] = fig2(torch, binding, wl, args.steps)
         save(args.out, "bench_fig2.json", line["fig2"])

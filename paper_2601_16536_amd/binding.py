@@ -46,6 +46,15 @@ class W4A16Error(RuntimeError):
 _lib = None
 
 
+def use_library(path: str) -> None:
+    """Loads another build of the library (the profiling build libw4a16_timeline.so) instead of libw4a16.so.
+    Only before the first call into the library."""
+    global LIB_PATH
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    LIB_PATH = path
+
+
 def lib():
     """The loaded library (raises if it has not been built)."""
     global _lib

@@ -18,6 +18,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libw4a16.so")
+TIMELINE_LIB = os.path.join(HERE, "libw4a16_timeline.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -29,8 +30,8 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def _compile(src: str, extra=()) -> str:
-    obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+def _compile(src: str, extra=(), objdir: str = OBJ) -> str:
+    obj = os.path.join(objdir, os.path.basename(src)[:-4] + ".o")
     cmd = [HIPCC, *FLAGS, *extra, "-c", src, "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
@@ -41,19 +42,24 @@ def _compile(src: str, extra=()) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(verbose: bool = True, timeline: bool = False) -> str:
+    """The library; timeline=True builds libw4a16_timeline.so instead, whose decode kernel records per-wave time
+    stamps of its phases (bench.py --timeline reads them).  The product never loads that one by itself."""
+    objdir = os.path.join(OBJ, "timeline") if timeline else OBJ
+    lib = TIMELINE_LIB if timeline else LIB
+    extra = ("-DW4A16_TIMELINE=1",) if timeline else ()
+    os.makedirs(objdir, exist_ok=True)
     srcs = sources()
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(_compile, srcs))
-    tmp = LIB + ".tmp%d" % os.getpid()
+        objs = list(ex.map(lambda src: _compile(src, extra, objdir), srcs))
+    tmp = lib + ".tmp%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":
-    build()
+    build(timeline="--timeline" in sys.argv[1:])
     sys.exit(0)

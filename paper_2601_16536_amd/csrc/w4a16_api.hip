@@ -57,7 +57,8 @@ struct Tuning {
     int stripe_waves = 0;   // waves per STRIPE workgroup
     int stripe_dyn = 0;     // M <= 4: 0/1 = units handed out by ticket (the default), 2 = equal contiguous runs per wave
     int stripe_unit = 0;    // packed rows per unit of the ticket form (2 or 4)
-    int stripe_depth = 0;   // units in flight per wave of the ticket form (1..4)
+    int stripe_depth = 0;   // units in flight per wave of the ticket form (1, 2; 9 = one, its successor requested ahead of use)
+    int stripe_dot2 = 0;    // 1: v_dot2_f32_f16 on the vector ALU instead of the MFMA (measurement only)
     int tile_rows = 0;      // rows of X per TILE workgroup (16, 32, 64)
     int tile_waves = 0;     // waves per TILE workgroup (4..8)
     int log = 0;            // 1: every call prints its plan on stderr
@@ -69,7 +70,8 @@ struct Knob {
 };
 const Knob kKnobs[] = {
     {"stripe_finish", &Tuning::stripe_finish}, {"stripe_waves", &Tuning::stripe_waves}, {"stripe_dyn", &Tuning::stripe_dyn},
-    {"stripe_unit", &Tuning::stripe_unit},     {"stripe_depth", &Tuning::stripe_depth}, {"tile_rows", &Tuning::tile_rows},
+    {"stripe_unit", &Tuning::stripe_unit},     {"stripe_depth", &Tuning::stripe_depth}, {"stripe_dot2", &Tuning::stripe_dot2},
+    {"tile_rows", &Tuning::tile_rows},
     {"tile_waves", &Tuning::tile_waves},       {"log", &Tuning::log},
 };
 
@@ -461,8 +463,8 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
         // measured on K = 4096 ... 28672 at M = 1, 2, 4: units of four packed rows, one in flight per wave, eight waves
         // (deeper rings, smaller or larger units, a successor requested ahead of use: all slower by 2 to 10 %)
         const int tu = tuning().stripe_unit, td = tuning().stripe_depth;
-        const int unit = tu == 2 ? 2 : (tu == 8 && group % 64 == 0 ? 8 : 4), depth = td >= 1 && td <= 4 ? td : (td == 9 ? 0 : 1);
-        e = launch_stripe_dyn(a, finish, b.sync, plan.waves_k, unit, depth, st);
+        const int unit = tu == 2 ? 2 : (tu == 8 && group % 64 == 0 ? 8 : 4), depth = td == 2 ? 2 : (td == 9 ? 0 : 1);
+        e = launch_stripe_dyn(a, finish, b.sync, plan.waves_k, unit, depth, tuning().stripe_dot2 == 1, st);
     } else if (plan.kernel == W4A16_KERNEL_STRIPE) {
         e = launch_stripe(a, finish, b.sync, plan.waves_k, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE) {

@@ -53,7 +53,8 @@ int stripe_min_waves(int M);
 int stripe_max_waves(int M);
 // STRIPE family for M <= 4: the slice is handed out to the waves in units of `unit_rows` packed rows (2 or 4) by an
 // LDS ticket counter, `depth` units in flight per wave; X, scales and zero points of the slice are staged in LDS.
-hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int unit_rows, int depth, hipStream_t stream);
+// `dot2`: the dot products on the vector ALU instead of the MFMA (measurement only).
+hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int unit_rows, int depth, bool dot2, hipStream_t stream);
 size_t stripe_dyn_lds_bytes(int M, int group, int groups_per_split);  // LDS one workgroup needs
 int stripe_dyn_lds_limit();                                           // most it may use
 // TILE family (the scheduler takes it for M >= 5): 64-column tiles, `rows_x` (16, 32 or 64) rows of X per

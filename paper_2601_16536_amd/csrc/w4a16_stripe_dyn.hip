@@ -40,7 +40,14 @@
 #include "w4a16_internal.h"
 
 #ifdef W4A16_TIMELINE
-__device__ unsigned long long *g_timeline;  // harness builds only: per-wave timestamps
+// Profiling build only (python -m paper_2601_16536_amd.build --timeline): per-wave time stamps of the kernel's
+// phases, eight 64-bit words per wave: kernel entry, first unit in use, loop end, workgroup's sums done, atomic
+// add back, exit, XCD id; 100 MHz ticks.  w4a16_timeline_buffer sets where they go (NULL = nowhere).
+__device__ unsigned long long *g_timeline;
+extern "C" int w4a16_timeline_buffer(void *device_words)
+{
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &device_words, sizeof device_words);
+}
 #endif
 
 namespace w4a16 {
@@ -77,7 +84,9 @@ __host__ __device__ inline Lds lds_layout(int mrows, int rows, int groups)
 
 // D units in flight per wave, a unit's successor requested when the unit has been used; or, AHEAD (D = 2 buffers):
 // one unit in flight, its successor requested just before the unit is used, so that a wave always has a request out.
-template <int MROWS, int U, int D, bool AHEAD>
+// DOT2: the dot products on the vector ALU (v_dot2_f32_f16, two k per instruction and row of X) instead of the MFMA:
+// the form a wavefront-level FMA design would take, kept for the measurement that decided against it.
+template <int MROWS, int U, int D, bool AHEAD, bool DOT2>
 __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -217,13 +226,38 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
 
     auto compute_unit = [&](uint4_t(&b)[U], int row) {
         float4_t part[4];
+        if constexpr (DOT2) {
 #pragma unroll
-        for (int t = 0; t < U; ++t) {
-            H8 x;
-            x.u = *reinterpret_cast<const uint4_t *>(smem + xa0 + (uint32_t)(row + t) * xstep);
+            for (int c = 0; c < 4; ++c) part[c] = zero4;
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                part[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, unpack8(b[t][c], masks), t == 0 ? zero4 : part[c], 0, 0, 0);
+            for (int t = 0; t < U; ++t) {
+                H8 w[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) w[c].h = unpack8(b[t][c], masks);
+#pragma unroll
+                for (int i = 0; i < MROWS; ++i) {
+                    H8 x;  // the same entry for every lane: an LDS broadcast
+                    x.u = *reinterpret_cast<const uint4_t *>(smem + L.xs + (uint32_t)((row + t) * MROWS + i) * 16u);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            H2 xp, wp;
+                            xp.u = x.u[h];
+                            wp.u = w[c].u[h];
+                            part[c][i] = __builtin_amdgcn_fdot2(xp.h, wp.h, part[c][i], false);
+                        }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                H8 x;
+                x.u = *reinterpret_cast<const uint4_t *>(smem + xa0 + (uint32_t)(row + t) * xstep);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    part[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, unpack8(b[t][c], masks), t == 0 ? zero4 : part[c], 0, 0, 0);
+            }
         }
         // the unit is done: scale and zero point (Eq. 2), then the exact sums
         const int g = (int)((uint32_t)row / (uint32_t)rpg);
@@ -346,18 +380,18 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
 
 int mrows_of(int M) { return M == 1 ? 1 : (M == 2 ? 2 : 4); }
 
-template <int MROWS, int U, int D, bool AHEAD>
+template <int MROWS, int U, int D, bool AHEAD, bool DOT2>
 hipError_t launch_m(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
 {
     const size_t lds = stripe_dyn_lds_bytes(a.M, a.group, a.groups_per_split);
     if (lds > (size_t)kLdsLimit) return hipErrorInvalidValue;
     const int nstripes = (a.N + kStripe - 1) / kStripe;
     if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_dyn_kernel<MROWS, U, D, AHEAD>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_dyn_kernel<MROWS, U, D, AHEAD, DOT2>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((stripe_dyn_kernel<MROWS, U, D, AHEAD>), dim3(a.split, nstripes), dim3(waves * 64), lds, stream, a, finish, sync);
+    hipLaunchKernelGGL((stripe_dyn_kernel<MROWS, U, D, AHEAD, DOT2>), dim3(a.split, nstripes), dim3(waves * 64), lds, stream, a, finish, sync);
     return hipGetLastError();
 }
 
@@ -371,7 +405,7 @@ size_t stripe_dyn_lds_bytes(int M, int group, int groups_per_split)
 int stripe_dyn_lds_limit() { return kLdsLimit; }
 
 // `finish` says how the slices meet (w4a16_finish.h); `sync` is the accumulator it may need.
-hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int unit_rows, int depth, hipStream_t stream)
+hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int unit_rows, int depth, bool dot2, hipStream_t stream)
 {
     if (a.M > 4 || a.group % 32 != 0 || waves < 1 || waves > 16) return hipErrorInvalidValue;
     if ((a.group / 8) % unit_rows != 0) return hipErrorInvalidValue;  // a unit never crosses a quantisation group
@@ -381,19 +415,17 @@ hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *
     if ((unsigned long long)a.M * a.K * 2ull >= 0x7F000000ull) return hipErrorInvalidValue;
     if ((a.N + kStripe - 1) / kStripe > 65535) return hipErrorInvalidValue;  // stripes are the grid's y
     // depth 0 = one unit in flight, its successor requested ahead of its use
-#define W4A16_DYN_CASE(MR, UU, DD) \
-    if (mrows_of(a.M) == MR && unit_rows == UU && depth == DD) return launch_m<MR, UU, (DD ? DD : 2), DD == 0>(a, finish, sync, waves, stream);
-#define W4A16_DYN_M(UU, DD) W4A16_DYN_CASE(1, UU, DD) W4A16_DYN_CASE(2, UU, DD) W4A16_DYN_CASE(4, UU, DD)
-    W4A16_DYN_M(4, 2)
-    W4A16_DYN_M(2, 2)
-    W4A16_DYN_M(4, 1)
-    W4A16_DYN_M(2, 3)
-    W4A16_DYN_M(4, 3)
-    W4A16_DYN_M(2, 4)
-    W4A16_DYN_M(8, 1)
-    W4A16_DYN_M(4, 0)
-    W4A16_DYN_M(2, 0)
-    W4A16_DYN_M(2, 1)
+#define W4A16_DYN_CASE(MR, UU, DD, DOT) \
+    if (mrows_of(a.M) == MR && unit_rows == UU && depth == DD && dot2 == DOT) \
+        return launch_m<MR, UU, (DD ? DD : 2), DD == 0, DOT>(a, finish, sync, waves, stream);
+#define W4A16_DYN_M(UU, DD, DOT) W4A16_DYN_CASE(1, UU, DD, DOT) W4A16_DYN_CASE(2, UU, DD, DOT) W4A16_DYN_CASE(4, UU, DD, DOT)
+    W4A16_DYN_M(4, 1, false)  // the scheduler's choice
+    W4A16_DYN_M(2, 1, false)  // the rest: for sweeps
+    W4A16_DYN_M(2, 2, false)
+    W4A16_DYN_M(4, 2, false)
+    W4A16_DYN_M(8, 1, false)
+    W4A16_DYN_M(4, 0, false)
+    W4A16_DYN_M(4, 1, true)
 #undef W4A16_DYN_M
 #undef W4A16_DYN_CASE
     return hipErrorInvalidValue;
