@@ -28,6 +28,10 @@
  *   zeros   uint32 [K/group, N/8] row-major.  The unsigned zero point (0..15,
  *                                 stored as itself) of n = 8c+j is bits
  *                                 4j..4j+3 of zeros[g, c].
+ *                                 `zeros` may be NULL: symmetric quantization
+ *                                 (Section 2.1: z = 0 on signed codes), read as
+ *                                 signed code = stored code - 8, i.e. every
+ *                                 zero point is 8 and no tensor is read.
  *   Y       FP16   [M, N]        row-major, every element overwritten.
  *
  * All data pointers are DEVICE pointers owned by the caller, 16-byte aligned;

@@ -107,10 +107,17 @@ def _stream(stream):
     return getattr(stream, "cuda_stream", stream)
 
 
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
 def _check_tensors(X, Wpacked, scales, zeros, group):
+    """zeros may be None: symmetric quantisation (every zero point is 8, no tensor)."""
     import torch
     for name, t, dt in (("X", X, torch.float16), ("Wpacked", Wpacked, torch.int32),
                         ("scales", scales, torch.float16), ("zeros", zeros, torch.int32)):
+        if t is None and name == "zeros":
+            continue
         if not t.is_cuda or not t.is_contiguous() or t.dtype != dt:
             raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (name, dt))
     M, K = X.shape
@@ -118,7 +125,7 @@ def _check_tensors(X, Wpacked, scales, zeros, group):
     if R * 8 != K or group < 1 or K % group:
         raise ValueError("Wpacked %r does not fit X %r / group %d" % (tuple(Wpacked.shape), tuple(X.shape), group))
     G = K // group
-    if tuple(scales.shape) != (G, N) or N % 8 or tuple(zeros.shape) != (G, N // 8):
+    if tuple(scales.shape) != (G, N) or N % 8 or (zeros is not None and tuple(zeros.shape) != (G, N // 8)):
         raise ValueError("scales/zeros shapes do not fit K=%d N=%d group=%d" % (K, N, group))
     return M, N, K
 
@@ -147,7 +154,7 @@ def gemm_noalloc(X, Wpacked, scales, zeros, group: int, out, kernel: int = KERNE
     M, N, K = _check_tensors(X, Wpacked, scales, zeros, group)
     if tuple(out.shape) != (M, N) or not out.is_contiguous():
         raise ValueError("out must be a contiguous [M, N] tensor")
-    rc = raw_gemm_noalloc(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, M, N, K,
+    rc = raw_gemm_noalloc(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), _ptr(zeros), group, M, N, K,
                           out.data_ptr(), _stream(stream), kernel, split)
     if rc:
         raise W4A16Error(rc, "w4a16_gemm_noalloc")
@@ -177,7 +184,7 @@ def gemm(X, Wpacked, scales, zeros, group: int, out=None, stream=None):
     import torch
     M, N, K = _check_tensors(X, Wpacked, scales, zeros, group)
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=X.device)
-    rc = raw_gemm(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, M, N, K,
+    rc = raw_gemm(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), _ptr(zeros), group, M, N, K,
                   Y.data_ptr(), _stream(stream))
     if rc:
         raise W4A16Error(rc, "w4a16_gemm")
@@ -189,7 +196,7 @@ def gemm_ex(X, Wpacked, scales, zeros, group: int, kernel: int = KERNEL_AUTO, sp
     import torch
     M, N, K = _check_tensors(X, Wpacked, scales, zeros, group)
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=X.device)
-    rc = raw_gemm_ex(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, M, N, K,
+    rc = raw_gemm_ex(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), _ptr(zeros), group, M, N, K,
                      Y.data_ptr(), _stream(stream), kernel, split)
     if rc:
         raise W4A16Error(rc, "w4a16_gemm_ex")
@@ -202,7 +209,7 @@ def gemm_ws(X, Wpacked, scales, zeros, group: int, workspace, kernel: int = KERN
     import torch
     M, N, K = _check_tensors(X, Wpacked, scales, zeros, group)
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=X.device)
-    rc = raw_gemm_ws(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, M, N, K,
+    rc = raw_gemm_ws(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), _ptr(zeros), group, M, N, K,
                      Y.data_ptr(), _stream(stream), kernel, split, workspace.data_ptr(),
                      workspace.numel() * workspace.element_size())
     if rc:
@@ -238,17 +245,18 @@ def reduce(partials, out=None, stream=None):
 def dequant(Wpacked, scales, zeros, group: int, out=None, stream=None):
     """Phase 1 alone (Algorithm 1): the FP16 matrix [K, N] of dequantised weights, for the unfused variant."""
     import torch
-    if not (Wpacked.is_cuda and scales.is_cuda and zeros.is_cuda):
+    tensors = [Wpacked, scales] + ([zeros] if zeros is not None else [])
+    if not all(t.is_cuda for t in tensors):
         raise TypeError("device tensors wanted")
-    if Wpacked.dtype != torch.int32 or zeros.dtype != torch.int32 or scales.dtype != torch.float16:
+    if Wpacked.dtype != torch.int32 or (zeros is not None and zeros.dtype != torch.int32) or scales.dtype != torch.float16:
         raise TypeError("Wpacked and zeros are int32 (uint32 bits), scales float16")
-    if not (Wpacked.is_contiguous() and scales.is_contiguous() and zeros.is_contiguous()):
+    if not all(t.is_contiguous() for t in tensors):
         raise TypeError("contiguous tensors wanted")
     K, N = Wpacked.shape[0] * 8, Wpacked.shape[1]
-    if K % group or tuple(scales.shape) != (K // group, N) or tuple(zeros.shape) != (K // group, N // 8):
+    if K % group or tuple(scales.shape) != (K // group, N) or (zeros is not None and tuple(zeros.shape) != (K // group, N // 8)):
         raise W4A16Error(2, "binding.dequant (shapes of scales / zeros)")
     W16 = out if out is not None else torch.empty((K, N), dtype=torch.float16, device=Wpacked.device)
-    rc = lib().w4a16_dequant(Wpacked.data_ptr(), scales.data_ptr(), zeros.data_ptr(), group, N, K, W16.data_ptr(),
+    rc = lib().w4a16_dequant(Wpacked.data_ptr(), scales.data_ptr(), _ptr(zeros), group, N, K, W16.data_ptr(),
                              _stream(stream))
     if rc:
         raise W4A16Error(rc, "w4a16_dequant")

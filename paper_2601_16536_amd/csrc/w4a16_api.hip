@@ -426,7 +426,7 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
         int K, void *Y, void *stream, int kernel, int split, Source src, void *call_ws, size_t call_ws_bytes)
 {
     t_hip_error[0] = 0;
-    if (!X || !Wp || !scales || !zeros || !Y) return W4A16_ERR_NULL;
+    if (!X || !Wp || !scales || !Y) return W4A16_ERR_NULL;  // zeros may be null: symmetric quantisation
     if (src == kFromCall && !call_ws) return W4A16_ERR_NULL;
     int rc = check_shape(group, M, N, K);
     if (rc) return rc;
@@ -566,7 +566,7 @@ int w4a16_dequant(const uint32_t *Wpacked, const void *scales, const uint32_t *z
                   void *W16, void *stream)
 {
     t_hip_error[0] = 0;
-    if (!Wpacked || !scales || !zeros || !W16) return W4A16_ERR_NULL;
+    if (!Wpacked || !scales || !W16) return W4A16_ERR_NULL;  // zeros may be null: symmetric quantisation
     int rc = check_shape(group, 1, N, K);
     if (rc) return rc;
     if (!aligned16(Wpacked) || !aligned16(scales) || !aligned16(zeros) || !aligned16(W16)) return W4A16_ERR_ALIGN;

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t *__restrict
     const int g = (r * 8) / group;
     const uint4_t w = *reinterpret_cast<const uint4_t *>(Wp + (size_t)r * N + c4);
     const uint2_t sc = *reinterpret_cast<const uint2_t *>(scales + (size_t)g * N + c4);
-    const uint32_t zw = Zp[(size_t)g * (N >> 3) + (c4 >> 3)] >> ((c4 & 4) * 4);
+    const uint32_t zw = (Zp ? Zp[(size_t)g * (N >> 3) + (c4 >> 3)] : 0x88888888u) >> ((c4 & 4) * 4);  // no tensor: symmetric, z = 8
     H2 s01, s23;
     s01.u = sc[0];
     s23.u = sc[1];

@@ -86,6 +86,12 @@ __device__ __forceinline__ float apply_scale_zero(float tot, float s, float z, f
     return __builtin_fmaf(s * 16777216.0f, P, __builtin_fmaf(-s * z, xsum, tot));
 }
 
+// Symmetric quantisation (Section 2.1: z = 0 on signed codes, i.e. 8 on the stored unsigned codes) comes without a
+// zero-point tensor.  The kernels then read their zero-point words through a buffer of size 0 (every load is out
+// of range: it returns 0 and moves nothing) and OR this word in: eight zero points of 8.
+__device__ __forceinline__ uint32_t symmetric_fill(const uint32_t *Zp) { return Zp ? 0u : 0x88888888u; }
+__device__ __forceinline__ uint32_t zero_point_bytes(const uint32_t *Zp, uint32_t bytes) { return Zp ? bytes : 0u; }
+
 __device__ __forceinline__ uint32_t pack_half2(float a, float b)
 {
     H2 p;

@@ -13,7 +13,7 @@ struct GemmArgs {
     const uint16_t *X;        // fp16 [M,K]
     const uint32_t *Wp;       // [K/8,N]
     const uint16_t *scales;   // fp16 [K/group,N]
-    const uint32_t *Zp;       // [K/group,N/8]
+    const uint32_t *Zp;       // [K/group,N/8], or null: symmetric quantisation, every zero point is 8
     uint16_t *Y;              // fp16 [M,N]
     float *partials;          // fp32 [S,M,N] (unused when split == 1)
     int group, M, N, K;

@@ -117,7 +117,8 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(a.scales) + (size_t)gbeg * a.N, 0, (uint32_t)groups * row_s, kRawBuffer);
     const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint32_t *>(a.Zp) + (size_t)gbeg * (a.N >> 3), 0, (uint32_t)groups * row_z, kRawBuffer);
+        const_cast<uint32_t *>(a.Zp) + (size_t)gbeg * (a.N >> 3), 0, zero_point_bytes(a.Zp, (uint32_t)groups * row_z), kRawBuffer);
+    const uint32_t zfill = symmetric_fill(a.Zp);
     const uint32_t vw = ok ? (uint32_t)col0 * 4u : kOutOfRange;
     const uint32_t vs = ok ? (uint32_t)col0 * 2u : kOutOfRange;
     const uint32_t vz = ok ? (uint32_t)(col0 >> 3) * 4u : kOutOfRange;
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
         const uint32_t base = valid ? b * kBlockRows * row_w : 0u;
         const uint32_t gu = __builtin_amdgcn_readfirstlane(valid ? g : 0u);  // wave-uniform: keeps the row offsets scalar
         r.sc = __builtin_amdgcn_raw_buffer_load_b64(rs, valid ? vs : kOutOfRange, gu * row_s, 0);
-        r.zw = __builtin_amdgcn_raw_buffer_load_b32(rz, valid ? vz : kOutOfRange, gu * row_z, 0);
+        r.zw = __builtin_amdgcn_raw_buffer_load_b32(rz, valid ? vz : kOutOfRange, gu * row_z, 0) | zfill;
 #pragma unroll
         for (int t = 0; t < kBlockRows; ++t)
             r.w[t] = __builtin_amdgcn_raw_buffer_load_b128(rw, valid ? vw : kOutOfRange, base + (uint32_t)t * row_w, 2);

@@ -136,7 +136,8 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(a.scales) + (size_t)gbeg * a.N, 0, (uint32_t)groups * (uint32_t)a.N * 2u, kRawBuffer);
     const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint32_t *>(a.Zp) + (size_t)gbeg * (a.N >> 3), 0, (uint32_t)groups * (uint32_t)(a.N >> 3) * 4u, kRawBuffer);
+        const_cast<uint32_t *>(a.Zp) + (size_t)gbeg * (a.N >> 3), 0, zero_point_bytes(a.Zp, (uint32_t)groups * (uint32_t)(a.N >> 3) * 4u), kRawBuffer);
+    const uint32_t zfill = symmetric_fill(a.Zp);
     auto x_offset = [&](int e) -> uint32_t {  // global byte offset of entry e of X, or out of range
         const uint32_t row = (uint32_t)e / MROWS, m = (uint32_t)e % MROWS;
         return (e < n_x && m < (uint32_t)a.M) ? (m * (uint32_t)a.K + ((uint32_t)row_base + row) * 8u) * 2u : kOutOfRange;
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
         *reinterpret_cast<float *>(smem + L.xsum + ((uint32_t)m * rows + row) * 4u) = sum8(d);
     };
     auto sc_put = [&](int e, uint4_t d) { if (e < n_sc) *reinterpret_cast<uint4_t *>(smem + L.sc + (uint32_t)e * 16u) = d; };
-    auto zp_put = [&](int e, uint4_t d) { if (e < n_zp) *reinterpret_cast<uint4_t *>(smem + L.zp + (uint32_t)e * 16u) = d; };
+    auto zp_put = [&](int e, uint4_t d) { if (e < n_zp) *reinterpret_cast<uint4_t *>(smem + L.zp + (uint32_t)e * 16u) = d | zfill; };
 
     uint4_t sx[kStage], ss[kStage], sz;
 #pragma unroll

@@ -106,7 +106,8 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int f
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(a.scales) + (size_t)gbeg * a.N, 0, (uint32_t)groups * row_s, kRawBuffer);
     const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint32_t *>(a.Zp) + (size_t)gbeg * (a.N >> 3), 0, (uint32_t)groups * row_z, kRawBuffer);
+        const_cast<uint32_t *>(a.Zp) + (size_t)gbeg * (a.N >> 3), 0, zero_point_bytes(a.Zp, (uint32_t)groups * row_z), kRawBuffer);
+    const uint32_t zfill = symmetric_fill(a.Zp);
     const uint32_t vw = ok ? (uint32_t)(g4 * a.N + col0) * 4u : kOutOfRange;
     const uint32_t vs = ok ? (uint32_t)col0 * 2u : kOutOfRange;
     const uint32_t vz = ok ? (uint32_t)(col0 >> 3) * 4u : kOutOfRange;
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int f
         const bool valid = b < wb1;
         const uint32_t gu = __builtin_amdgcn_readfirstlane(valid ? g : 0u);  // wave-uniform: keeps the row offsets scalar
         r.sc = __builtin_amdgcn_raw_buffer_load_b64(rs, vs, gu * row_s, 0);   // past the run: group 0 again, unused
-        r.zw = __builtin_amdgcn_raw_buffer_load_b32(rz, vz, gu * row_z, 0);
+        r.zw = __builtin_amdgcn_raw_buffer_load_b32(rz, vz, gu * row_z, 0) | zfill;
         r.w = __builtin_amdgcn_raw_buffer_load_b128(rw, valid ? vw : kOutOfRange, valid ? b * kBlockRows * row_w : 0u, 2);
     };
 
@@ -337,7 +338,8 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(a.scales) + (size_t)g0 * a.N, 0, (uint32_t)ng * row_s, kRawBuffer);
     const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint32_t *>(a.Zp) + (size_t)g0 * (a.N >> 3), 0, (uint32_t)ng * row_z, kRawBuffer);
+        const_cast<uint32_t *>(a.Zp) + (size_t)g0 * (a.N >> 3), 0, zero_point_bytes(a.Zp, (uint32_t)ng * row_z), kRawBuffer);
+    const uint32_t zfill = symmetric_fill(a.Zp);
     // running per-lane offsets of the next block / group to load; the range check is on these
     uint32_t vw = ok ? (uint32_t)(g4 * a.N + col0) * 4u : kOutOfRange;
     uint32_t vs = ok ? (uint32_t)col0 * 2u : kOutOfRange;
@@ -417,7 +419,7 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
             // The group's scales and zero points, wanted when its four blocks are done.  Loads return in order:
             // these come in behind the weights of the groups in flight, which are wanted earlier anyway.
             const uint2_t sc = __builtin_amdgcn_raw_buffer_load_b64(rs, vs, 0, 0);
-            const uint32_t zw = __builtin_amdgcn_raw_buffer_load_b32(rz, vz, 0, 0);
+            const uint32_t zw = __builtin_amdgcn_raw_buffer_load_b32(rz, vz, 0, 0) | zfill;
             vs += row_s;
             vz += row_z;
 #pragma unroll

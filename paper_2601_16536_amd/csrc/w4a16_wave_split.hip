@@ -58,6 +58,7 @@ struct Streams {
     uint32_t vw, vs, vz;             // this lane's byte offsets inside a unit / scale row / zero row
     uint32_t unit_w, row_w;          // bytes per unit and per packed row of Wp
     uint32_t row_s, row_z;           // bytes per row of scales / zeros
+    uint32_t zfill;                  // ORed into every zero-point word: 0, or eight 8s without a zero-point tensor
 };
 
 // Loads unit `u` (relative to the workgroup's slice) if u < end, else nothing
@@ -84,7 +85,7 @@ __device__ __forceinline__ void load_unit(Unit<STEPS, VEC> &r, const Streams &st
     } else {
         r.sc[0] = __builtin_amdgcn_raw_buffer_load_b32(st.s, vs, g * st.row_s, 0);
     }
-    r.zw = __builtin_amdgcn_raw_buffer_load_b32(st.z, vz, g * st.row_z, 0);
+    r.zw = __builtin_amdgcn_raw_buffer_load_b32(st.z, vz, g * st.row_z, 0) | st.zfill;
 }
 
 template <int MROWS, int STEPS, int VEC>
@@ -205,7 +206,8 @@ __global__ __launch_bounds__(kWaves * 64) void wave_split_kernel(const GemmArgs 
     st.s = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(a.scales) + (size_t)gbeg * a.N, 0,
                                              (uint32_t)(gend - gbeg) * st.row_s, kRawBuffer);
     st.z = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.Zp) + (size_t)gbeg * (a.N >> 3), 0,
-                                             (uint32_t)(gend - gbeg) * st.row_z, kRawBuffer);
+                                             zero_point_bytes(a.Zp, (uint32_t)(gend - gbeg) * st.row_z), kRawBuffer);
+    st.zfill = symmetric_fill(a.Zp);
     st.vw = ok ? (uint32_t)(g4 * a.N + col0) * 4u : kOutOfRange;
     st.vs = ok ? (uint32_t)col0 * 2u : kOutOfRange;
     st.vz = ok ? (uint32_t)(col0 >> 3) * 4u : kOutOfRange;
