@@ -210,6 +210,8 @@ int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, 
  *   "stripe_depth"   units in flight per wave (1, 2; 9 = one, its successor requested ahead of its use)
  *   "stripe_dot2"    1: dot products by v_dot2_f32_f16 on the vector ALU instead of the MFMA (measurement only)
  *   "tile_rows"      rows of X per TILE workgroup (16, 32, 64)
+ *   "tile_dyn"       16 rows of X per workgroup: 1 = units of K always handed out by ticket, 2 = never
+ *   "tile_depth"     units in flight per wave of that form (1, 2)
  *   "tile_waves"     waves per TILE workgroup (4..8)
  *   "log"            1: every w4a16_gemm* call prints its plan on stderr (the one case in which the library prints)
  * Returns W4A16_ERR_UNSUPPORTED for an unknown knob.

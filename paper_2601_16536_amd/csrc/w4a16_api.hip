@@ -60,6 +60,8 @@ struct Tuning {
     int stripe_depth = 0;   // units in flight per wave of the ticket form (1, 2; 9 = one, its successor requested ahead of use)
     int stripe_dot2 = 0;    // 1: v_dot2_f32_f16 on the vector ALU instead of the MFMA (measurement only)
     int tile_rows = 0;      // rows of X per TILE workgroup (16, 32, 64)
+    int tile_dyn = 0;       // 16 rows of X per workgroup: 1 = units always handed out by ticket, 2 = never (equal runs per wave)
+    int tile_depth = 0;     // units in flight per wave of the ticket form (1, 2)
     int tile_waves = 0;     // waves per TILE workgroup (4..8)
     int log = 0;            // 1: every call prints its plan on stderr
 };
@@ -71,7 +73,7 @@ struct Knob {
 const Knob kKnobs[] = {
     {"stripe_finish", &Tuning::stripe_finish}, {"stripe_waves", &Tuning::stripe_waves}, {"stripe_dyn", &Tuning::stripe_dyn},
     {"stripe_unit", &Tuning::stripe_unit},     {"stripe_depth", &Tuning::stripe_depth}, {"stripe_dot2", &Tuning::stripe_dot2},
-    {"tile_rows", &Tuning::tile_rows},
+    {"tile_rows", &Tuning::tile_rows},         {"tile_dyn", &Tuning::tile_dyn},         {"tile_depth", &Tuning::tile_depth},
     {"tile_waves", &Tuning::tile_waves},       {"log", &Tuning::log},
 };
 
@@ -183,6 +185,9 @@ size_t workspace_of(int kernel, int M, int N, int S)
 }
 
 bool stripe_by_ticket(int M) { return M <= 4 && tuning().stripe_dyn != 2; }
+// TILE with one block of 16 rows of X: the ticket form (measured 1 to 6 % faster than equal runs per wave at M <= 16;
+// with several row blocks, which re-read the weights from the L2, 3 % slower).
+bool tile_by_ticket(int M, int rows_x) { return rows_x == 16 && (tuning().tile_dyn == 1 || (M <= 16 && tuning().tile_dyn != 2)); }
 
 // LDS a STRIPE workgroup needs for a slice of gps groups, and the most it may use.
 size_t stripe_lds(int M, int group, int gps, int waves)
@@ -259,7 +264,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         if (tr == 16 || tr == 32 || tr == 64) rows_x = tr;
         p->tile_m = rows_x;
         const int tw = tuning().tile_waves;
-        if (tw >= 4 && tw <= 8) { p->waves_k = tw; p->threads = 64 * tw; }
+        if (tw >= 4 && tw <= (tile_by_ticket(M, rows_x) ? 16 : 8)) { p->waves_k = tw; p->threads = 64 * tw; }
         const long long wgs = tiles * ((M + rows_x - 1) / rows_x);
         if (S == 0) S = (int)(cus / wgs);  // never more workgroups than compute units: the extra ones would run as a second round
         if (S < 1) S = 1;
@@ -467,6 +472,8 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
         e = launch_stripe_dyn(a, finish, b.sync, plan.waves_k, unit, depth, tuning().stripe_dot2 == 1, st);
     } else if (plan.kernel == W4A16_KERNEL_STRIPE) {
         e = launch_stripe(a, finish, b.sync, plan.waves_k, st);
+    } else if (plan.kernel == W4A16_KERNEL_TILE && tile_by_ticket(M, plan.tile_m)) {
+        e = launch_tile_dyn(a, finish, b.sync, plan.waves_k, tuning().tile_depth == 2 ? 2 : 1, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE) {
         e = launch_tile(a, finish, b.sync, plan.tile_m, plan.waves_k, st);
     } else {

@@ -61,6 +61,9 @@ int stripe_dyn_lds_limit();                                           // most it
 // workgroup, `waves` (4..8) waves per workgroup that split the K slice; `finish` and `sync` as in the STRIPE
 // family.
 hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, int waves, hipStream_t stream);
+// TILE family, 16 rows of X per workgroup, the slice handed out to the waves by ticket (w4a16_tile_dyn.hip); `depth` (1, 2)
+// units in flight per wave.
+hipError_t launch_tile_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int depth, hipStream_t stream);
 // Clears n words of a fixed-point accumulator.
 hipError_t launch_accumulator_clear(unsigned long long *acc, size_t n, hipStream_t stream);
 // Phase 1 alone (Algorithm 1): W16[K, N] = fp16(s (q - z)) in global memory, for the unfused variant.
