@@ -216,6 +216,51 @@ int w4a16_oracle_gemm_symmetric(const uint16_t *X, const uint32_t *Wp,
     return 0;
 }
 
+/* BF16 activations.  The paper's A is "16-bit floating point"; its own runs use
+ * FP16, BF16 is the other 16-bit format models ship in.  A bfloat16 is the
+ * upper half of a binary32: sign, the same 8 exponent bits, the top 7
+ * fraction bits.  Decoded here field by field (not by a bit cast), so that a
+ * mistake in either would show. */
+float w4a16_oracle_bfloat_to_float(uint16_t b)
+{
+    uint32_t negative = (uint32_t)(b >> 15) & 1u;
+    uint32_t biased = (uint32_t)(b >> 7) & 0xFFu;
+    uint32_t mant = (uint32_t)b & 0x7Fu;
+    float val;
+    if (biased == 0) {
+        /* zero or subnormal: mant * 2^-133 */
+        val = ldexpf((float)mant, -133);
+    } else if (biased == 255) {
+        val = mant ? nanf("") : INFINITY;
+    } else {
+        /* (128 + mant) * 2^(biased - 134) */
+        val = ldexpf((float)(128u + mant), (int)biased - 134);
+    }
+    return negative ? -val : val;
+}
+
+/* ref[M,N] (binary64) <- A * Dequant(W) (Eq. 2) with A given as bfloat16 bit
+ * patterns; W, s, z exactly as in the FP16 form (the scales stay FP16: they
+ * belong to the quantized weights).  A bfloat16 (8 significant bits) times a
+ * 15-bit binary32 weight is exact in binary64; only the additions round. */
+int w4a16_oracle_gemm_bf16(const uint16_t *Xb, const uint32_t *Wp,
+                           const uint16_t *scales, const uint32_t *Zp,
+                           int group, int M, int N, int K, double *ref)
+{
+    if (!shape_ok(group, M, N, K)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            double total = 0.0;
+            for (int kk = 0; kk < K; ++kk) {
+                double xb = (double)w4a16_oracle_bfloat_to_float(Xb[(size_t)m * K + kk]);
+                total += xb * (double)weight_at(Wp, scales, Zp, group, N, kk, n);
+            }
+            ref[(size_t)m * N + n] = total;
+        }
+    return 0;
+}
+
 /* Threads the gemm above spreads its columns over. */
 int w4a16_oracle_threads(void)
 {

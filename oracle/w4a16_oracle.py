@@ -55,6 +55,9 @@ def _load():
         lib.w4a16_oracle_gemm_columns.argtypes = [u16p, u32p, u16p, u32p, ci, ci, ci, ci, i32p, ci, f64p]
         lib.w4a16_oracle_dequant_symmetric.argtypes = [u32p, u16p, ci, ci, ci, f32p]
         lib.w4a16_oracle_gemm_symmetric.argtypes = [u16p, u32p, u16p, ci, ci, ci, ci, f64p]
+        lib.w4a16_oracle_bfloat_to_float.argtypes = [ctypes.c_uint16]
+        lib.w4a16_oracle_bfloat_to_float.restype = ctypes.c_float
+        lib.w4a16_oracle_gemm_bf16.argtypes = [u16p, u32p, u16p, u32p, ci, ci, ci, ci, f64p]
         lib.w4a16_oracle_threads.argtypes = []
         _lib = lib
     return _lib
@@ -187,6 +190,53 @@ def gemm_symmetric(X, Wp, scales, group: int) -> np.ndarray:
                                            group, X.shape[0], N, K, _ptr(ref, ctypes.c_double)):
         raise ValueError("oracle rejected the arguments")
     return ref
+
+
+def bfloat_to_float(bits: int) -> np.float32:
+    """bfloat16 bit pattern -> binary32 value, by the oracle's own field-by-field decoding."""
+    return np.float32(_load().w4a16_oracle_bfloat_to_float(int(bits) & 0xFFFF))
+
+
+def gemm_bf16(Xb, Wp, scales, Zp, group: int) -> np.ndarray:
+    """ref = A * Dequant(W) (Eq. 2) in binary64 [M, N], A given as bfloat16 bit patterns (uint16 [M, K])."""
+    Wp, s, Zp, K, N = _check(Wp, scales, Zp, group)
+    Xb = np.ascontiguousarray(Xb)
+    if Xb.dtype != np.uint16 or Xb.ndim != 2 or Xb.shape[1] != K:
+        raise ValueError("X must be uint16 bfloat16 bit patterns [M, %d], got %s %r" % (K, Xb.dtype, Xb.shape))
+    ref = np.empty((Xb.shape[0], N), np.float64)
+    if _load().w4a16_oracle_gemm_bf16(_ptr(Xb, ctypes.c_uint16), _ptr(Wp, ctypes.c_uint32), _ptr(s, ctypes.c_uint16),
+                                      _ptr(Zp, ctypes.c_uint32), group, Xb.shape[0], N, K, _ptr(ref, ctypes.c_double)):
+        raise ValueError("oracle rejected the arguments")
+    return ref
+
+
+def to_bf16_bits(ref: np.ndarray) -> np.ndarray:
+    """Final cast of Section 3 for a bfloat16 output: binary64 -> bfloat16 bit patterns, one rounding
+    (to nearest, ties to even), written out on the value: v = f 2^e with 1/2 <= |f| < 1 keeps 8 significant
+    bits, i.e. a multiple of 2^(e-8); below the normal range the spacing stays 2^-133; beyond the largest
+    finite bfloat16 the result is an infinity."""
+    v = np.asarray(ref, dtype=np.float64)
+    out = np.zeros(v.shape, np.uint16)
+    sign = np.signbit(v).astype(np.uint16) << 15
+    a = np.abs(v)
+    nan = np.isnan(v)
+    with np.errstate(invalid="ignore", over="ignore"):
+        f, e = np.frexp(np.where(np.isfinite(a), a, 0.0))
+        e = np.maximum(e, -125)                      # normal range starts at 2^-126 = 0.5 * 2^-125
+        steps = np.rint(np.ldexp(a, 8 - e))          # multiples of the spacing 2^(e-8); rint is ties-to-even
+        steps = np.where(np.isfinite(a), steps, 0.0).astype(np.int64)
+    # steps in 0..256: 0..127 subnormal (e = -125), 128..255 the significand, 256 = carry into the next binade
+    carry = steps == 256
+    e = np.where(carry, e + 1, e)
+    steps = np.where(carry, 128, steps)
+    biased = np.where(steps < 128, 0, e + 126)       # value = steps * 2^(e-8) = (128 + mant) 2^(biased-134)
+    mant = np.where(steps < 128, steps, steps - 128)
+    inf = np.isinf(a) | (biased >= 255)
+    bits = (biased.astype(np.int64) << 7) | mant
+    bits = np.where(inf, 0x7F80, bits)
+    bits = np.where(nan, 0x7FC0, bits)
+    out[...] = bits.astype(np.uint16) | sign
+    return out
 
 
 def to_fp16(ref: np.ndarray) -> np.ndarray:

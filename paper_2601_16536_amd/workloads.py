@@ -119,6 +119,16 @@ def make_x(M: int, K: int, index: int, outliers: bool = False) -> np.ndarray:
     return x.astype(np.float16)
 
 
+def make_x_bf16(M: int, K: int, index: int, outliers: bool = False) -> np.ndarray:
+    """The same draw as make_x, stored as bfloat16 bit patterns (uint16): the binary32 value's upper half,
+    the lower 16 bits dropped (a storage choice of this generator, no rounding rule involved)."""
+    x = _rng(index, 0).standard_normal((M, K))
+    if outliers:
+        ch = _rng(index, 4).choice(K, size=K // 100, replace=False)
+        x[:, ch] *= 20.0
+    return (x.astype(np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
 def make_weights(K: int, N: int, index: int, group: int = GROUP):
     """Returns (Wp, scales, Zp) in the storage layout above."""
     if K % group or K % 8 or N % 8:

@@ -4,6 +4,11 @@ Symmetric quantization (Section 2.1: z = 0 in Eq. 1, on signed codes; here the s
 minus 8 and there is no zero-point tensor): exact rationals on every weight, brute force with rationals on tiny
 shapes, the closed form for a constant code, a BLAS GEMM on weights the test builds itself, agreement with the
 general oracle fed an explicit zero-point tensor of eights (a different code path), and planted mistakes.
+
+BF16 activations (the paper's A is a 16-bit float; bfloat16 is the upper half of a binary32): the decoding against
+the bit cast and against a library's conversion on all 65536 patterns, the format's landmark values, brute force
+with rationals, a BLAS GEMM, bit-equality with the FP16 oracle on inputs both formats hold, and the output rounding
+against exact rationals, a library's cast and the case where rounding twice would differ.
 """
 import os
 import subprocess
@@ -79,7 +84,105 @@ def test_symmetric_equals_general_oracle_with_zero_point_eight():
     assert np.array_equal(orc.dequant_symmetric(Wp, s, group), orc.dequant(Wp, s, Zp, group))
 
 
+def _bf16_values(bits):
+    """bfloat16 patterns -> binary32 by the bit cast (the format's definition: the upper half of a binary32)."""
+    return (np.asarray(bits, np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def test_bfloat_decoding_all_patterns():
+    import torch
+    allb = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    mine = np.array([orc.bfloat_to_float(int(b)) for b in allb], np.float32)
+    cast = _bf16_values(allb)
+    lib = torch.from_numpy(allb.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
+    fin = ~np.isnan(cast)
+    assert np.array_equal(np.isnan(mine), np.isnan(cast)) and np.array_equal(np.isnan(lib), np.isnan(cast))
+    assert np.array_equal(mine[fin].view(np.uint32), cast[fin].view(np.uint32))  # signed zeros included
+    assert np.array_equal(lib[fin].view(np.uint32), cast[fin].view(np.uint32))
+    # landmarks of the format (1 sign, 8 exponent, 7 fraction bits, bias 127)
+    for bits, value in ((0x3F80, 1.0), (0x4049, 3.140625), (0xC2F7, -123.5), (0x0001, 2.0 ** -133), (0x0080, 2.0 ** -126),
+                        (0x7F7F, (2 - 2.0 ** -7) * 2.0 ** 127), (0x3C00, 2.0 ** -7), (0xBF00, -0.5)):
+        assert float(orc.bfloat_to_float(bits)) == value, hex(bits)
+    assert np.isinf(orc.bfloat_to_float(0x7F80)) and orc.bfloat_to_float(0xFF80) < 0
+
+
+@pytest.mark.parametrize("M,K,N,group", [(2, 16, 8, 8), (3, 256, 16, 128), (1, 64, 8, 32)])
+def test_bf16_brute_force_rationals(M, K, N, group):
+    _, Wp, s, Zp = wl.make(M, K, N, index=740 + K, group=group)
+    Xb = wl.make_x_bf16(M, K, index=740 + K)
+    ref = orc.gemm_bf16(Xb, Wp, s, Zp, group)
+    xv = _bf16_values(Xb)
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(0)
+            for k in range(K):
+                qv = (int(Wp[k // 8, n]) >> (4 * (k % 8))) & 15
+                zv = (int(Zp[k // group, n // 8]) >> (4 * (n % 8))) & 15
+                acc += Fraction(float(xv[m, k])) * Fraction(float(s[k // group, n])) * (qv - zv)
+            want = float(acc)
+            assert abs(ref[m, n] - want) <= 1e-13 * (1 + abs(want)), (m, n)
+
+
+def test_bf16_is_a_plain_gemm():
+    rng = np.random.default_rng(75)
+    M, K, N, group = 5, 1024, 40, 64
+    q = rng.integers(0, 16, (K, N))
+    z = rng.integers(0, 16, (K // group, N))
+    s = rng.uniform(0.001, 0.02, (K // group, N)).astype(np.float16)
+    Xb = wl.make_x_bf16(M, K, index=75, outliers=True)
+    ref = orc.gemm_bf16(Xb, wl.pack_along_k(q.astype(np.uint8)), s, wl.pack_along_n(z.astype(np.uint8)), group)
+    want = _bf16_values(Xb).astype(np.float64) @ ((q - np.repeat(z, group, axis=0)) * np.repeat(s.astype(np.float64), group, axis=0))
+    assert np.allclose(ref, want, rtol=1e-11, atol=1e-12)
+
+
+def test_bf16_equals_the_fp16_oracle_where_both_formats_hold_x():
+    """Values with 8 significant bits and a modest exponent are both an FP16 and a bfloat16: the two oracles
+    (different decoders) must then agree bit for bit."""
+    M, K, N, group = 4, 768, 24, 128
+    _, Wp, s, Zp = wl.make(M, K, N, index=76, group=group)
+    Xb = wl.make_x_bf16(M, K, index=76)
+    xv = _bf16_values(Xb)
+    keep = (np.abs(xv) >= 2.0 ** -14) & (np.abs(xv) < 60000)
+    Xb = np.where(keep, Xb, 0).astype(np.uint16)
+    xh = _bf16_values(Xb).astype(np.float16)
+    assert np.array_equal(xh.astype(np.float32), _bf16_values(Xb))
+    assert np.array_equal(orc.gemm_bf16(Xb, Wp, s, Zp, group), orc.gemm(xh, Wp, s, Zp, group))
+
+
+def test_bf16_output_rounding():
+    import torch
+    rng = np.random.default_rng(77)
+    v32 = (rng.standard_normal(200000) * 10.0 ** rng.integers(-44, 39, 200000)).astype(np.float32)
+    v32 = np.concatenate([v32, np.array([0.0, -0.0, np.inf, -np.inf, 1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 2.0 ** -133, 2.0 ** -134,
+                                         1.5 * 2.0 ** -134, 2.0 ** -126, 3.3895313892515355e38, 3.39e38, 3.4e38], np.float32)])
+    got = orc.to_bf16_bits(v32.astype(np.float64))
+    lib = torch.from_numpy(v32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, lib)
+    assert orc.to_bf16_bits(np.array([np.nan]))[0] & 0x7FFF > 0x7F80
+    # ties go to the even significand; one rounding only: 1 + 2^-8 + 2^-40 is above the tie, although its
+    # binary32 rounding sits exactly on it
+    assert orc.to_bf16_bits(np.array([1 + 2.0 ** -8]))[0] == 0x3F80
+    assert orc.to_bf16_bits(np.array([1 + 3 * 2.0 ** -8]))[0] == 0x3F82
+    assert orc.to_bf16_bits(np.array([1 + 2.0 ** -8 + 2.0 ** -40]))[0] == 0x3F81
+    # nearest, against exact rationals: no neighbouring pattern is closer
+    v64 = rng.standard_normal(3000) * 10.0 ** rng.integers(-30, 30, 3000)
+    bits = orc.to_bf16_bits(v64)
+    for v, b in zip(v64, bits):
+        mine = abs(Fraction(float(_bf16_values([b])[0])) - Fraction(v))
+        for nb in (int(b) - 1, int(b) + 1):
+            other = float(_bf16_values([nb & 0xFFFF])[0])
+            if np.isfinite(other):
+                assert mine <= abs(Fraction(other) - Fraction(v))
+
+
 MUTANTS = [
+    ("bias of the bfloat16 exponent", "(int)biased - 134);", "(int)biased - 133);"),
+    ("bfloat16 subnormal spacing", "ldexpf((float)mant, -133);", "ldexpf((float)mant, -134);"),
+    ("bfloat16 fraction width", "uint32_t mant = (uint32_t)b & 0x7Fu;", "uint32_t mant = (uint32_t)b & 0x3Fu;"),
+    ("bfloat16 hidden bit", "(float)(128u + mant)", "(float)(mant)"),
+    ("bf16 narrow sum", "double total = 0.0;", "float total = 0.0f;"),
+    ("bf16 dropped last term", "for (int kk = 0; kk < K; ++kk) {", "for (int kk = 0; kk < K - 1; ++kk) {"),
+    ("bf16 row stride of X", "Xb[(size_t)m * K + kk]", "Xb[(size_t)m * (K - 8) + kk]"),
     ("offset of the signed code", "int signed_code = code_at(Wp, N, k, n) - 8;", "int signed_code = code_at(Wp, N, k, n) - 7;"),
     ("sign of the offset", "int signed_code = code_at(Wp, N, k, n) - 8;", "int signed_code = 8 - code_at(Wp, N, k, n);"),
     ("group of the scale", "int grp = k / group;", "int grp = k / 128;"),
