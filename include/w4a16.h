@@ -145,6 +145,20 @@ int w4a16_gemm_ws(const void *X, const uint32_t *Wpacked, const void *scales, co
                   void *workspace, size_t workspace_bytes);
 
 /*
+ * The same operation with BF16 activations: X [M, K] and Y [M, N] are bfloat16 (the upper half of a binary32),
+ * everything that belongs to the quantized weights is unchanged (packed codes, FP16 scales, packed zero points
+ * or NULL).  Algorithm 1 lists A and C as 16-bit floating point; the paper's runs use FP16, this entry covers
+ * the other 16-bit format (bf16 MFMA, FP32 sums, one round-to-nearest-even cast at the end).  Arguments, split
+ * buffers, stream rules and errors as w4a16_gemm_ex; kernel = W4A16_KERNEL_AUTO and split = 0 give the
+ * scheduler's plan (the same plan as for FP16).  Forced plans: W4A16_KERNEL_TILE for any M,
+ * W4A16_KERNEL_STRIPE for M <= 4; the others return W4A16_ERR_UNSUPPORTED.  Results beyond +-2^25 saturate
+ * there when K slices meet in the fixed-point accumulator or when the waves of a workgroup share a slice by
+ * ticket (M <= 16), as for FP16, where that bound lies beyond the format's range.
+ */
+int w4a16_gemm_bf16(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros,
+                    int group, int M, int N, int K, void *Y, void *stream, int kernel, int split);
+
+/*
  * Registers caller-owned split buffers (Algorithm 1's C_i; Section 3) for the
  * current device: device memory, 256-byte aligned, at least 256 bytes, owned by
  * the caller and kept valid until it is replaced or removed (NULL removes it).

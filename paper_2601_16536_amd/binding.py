@@ -16,7 +16,7 @@ ERR_NULL, ERR_SHAPE, ERR_GROUP, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORT
 KERNEL_AUTO, KERNEL_WAVE_SPLIT, KERNEL_STRIPE, KERNEL_TILE = -1, 0, 3, 4  # 1 and 2: retired families
 
 EXPORTS = (
-    "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_gemm_noalloc", "w4a16_set_workspace", "w4a16_tune",
+    "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_gemm_noalloc", "w4a16_gemm_bf16", "w4a16_set_workspace", "w4a16_tune",
     "w4a16_workspace_bytes", "w4a16_query_plan",
     "w4a16_reduce", "w4a16_dequant", "w4a16_quantize", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
 )
@@ -74,6 +74,7 @@ def lib():
         L.w4a16_gemm_ex.argtypes = gemm_args + [ci, ci]
         L.w4a16_gemm_ws.argtypes = gemm_args + [ci, ci, vp, sz]
         L.w4a16_gemm_noalloc.argtypes = gemm_args + [ci, ci]
+        L.w4a16_gemm_bf16.argtypes = gemm_args + [ci, ci]
         L.w4a16_set_workspace.argtypes = [vp, sz]
         L.w4a16_tune.argtypes = [ctypes.c_char_p, ci]
         L.w4a16_workspace_bytes.argtypes = [ci, ci, ci, ci]
@@ -111,10 +112,10 @@ def _ptr(t) -> int:
     return 0 if t is None else t.data_ptr()
 
 
-def _check_tensors(X, Wpacked, scales, zeros, group):
+def _check_tensors(X, Wpacked, scales, zeros, group, x_dtype=None):
     """zeros may be None: symmetric quantisation (every zero point is 8, no tensor)."""
     import torch
-    for name, t, dt in (("X", X, torch.float16), ("Wpacked", Wpacked, torch.int32),
+    for name, t, dt in (("X", X, x_dtype or torch.float16), ("Wpacked", Wpacked, torch.int32),
                         ("scales", scales, torch.float16), ("zeros", zeros, torch.int32)):
         if t is None and name == "zeros":
             continue
@@ -200,6 +201,20 @@ def gemm_ex(X, Wpacked, scales, zeros, group: int, kernel: int = KERNEL_AUTO, sp
                      Y.data_ptr(), _stream(stream), kernel, split)
     if rc:
         raise W4A16Error(rc, "w4a16_gemm_ex")
+    return Y
+
+
+def gemm_bf16(X, Wpacked, scales, zeros, group: int, kernel: int = KERNEL_AUTO, split: int = 0, out=None, stream=None):
+    """w4a16_gemm_bf16: X and the result are torch.bfloat16; the weights' tensors as in gemm."""
+    import torch
+    M, N, K = _check_tensors(X, Wpacked, scales, zeros, group, torch.bfloat16)
+    Y = out if out is not None else torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    if Y.dtype != torch.bfloat16 or tuple(Y.shape) != (M, N) or not Y.is_contiguous():
+        raise ValueError("out must be a contiguous bfloat16 [M, N] tensor")
+    rc = lib().w4a16_gemm_bf16(X.data_ptr(), Wpacked.data_ptr(), scales.data_ptr(), _ptr(zeros), group, M, N, K,
+                               Y.data_ptr(), _stream(stream), kernel, split)
+    if rc:
+        raise W4A16Error(rc, "w4a16_gemm_bf16")
     return Y
 
 

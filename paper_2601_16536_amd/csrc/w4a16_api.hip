@@ -428,7 +428,7 @@ void log_plan(const char *entry, int M, int N, int K, int group, const w4a16_pla
 }
 
 int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales, const uint32_t *zeros, int group, int M, int N,
-        int K, void *Y, void *stream, int kernel, int split, Source src, void *call_ws, size_t call_ws_bytes)
+        int K, void *Y, void *stream, int kernel, int split, Source src, void *call_ws, size_t call_ws_bytes, bool bf16 = false)
 {
     t_hip_error[0] = 0;
     if (!X || !Wp || !scales || !Y) return W4A16_ERR_NULL;  // zeros may be null: symmetric quantisation
@@ -443,6 +443,9 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
     w4a16_plan plan;
     rc = make_plan(M, N, K, group, kernel, split, compute_units(dev), &plan);
     if (rc) return rc;
+    // bfloat16 activations: the forms the scheduler chooses from (STRIPE by ticket for M <= 4, TILE)
+    if (bf16 && (plan.kernel == W4A16_KERNEL_WAVE_SPLIT || (plan.kernel == W4A16_KERNEL_STRIPE && !stripe_by_ticket(M))))
+        return W4A16_ERR_UNSUPPORTED;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int finish = finish_of(plan.kernel, M, N, plan.split);
@@ -462,6 +465,7 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
     a.split = plan.split;
     a.groups_per_split = plan.groups_per_split;
     a.groups = K / group;
+    a.bf16 = bf16 ? 1 : 0;
 
     hipError_t e;
     if (plan.kernel == W4A16_KERNEL_STRIPE && stripe_by_ticket(M)) {
@@ -469,17 +473,20 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
         // (deeper rings, smaller or larger units, a successor requested ahead of use: all slower by 2 to 10 %)
         const int tu = tuning().stripe_unit, td = tuning().stripe_depth;
         const int unit = tu == 2 ? 2 : (tu == 8 && group % 64 == 0 ? 8 : 4), depth = td == 2 ? 2 : (td == 9 ? 0 : 1);
-        e = launch_stripe_dyn(a, finish, b.sync, plan.waves_k, unit, depth, tuning().stripe_dot2 == 1, st);
+        if (bf16)
+            e = launch_stripe_dyn(a, finish, b.sync, plan.waves_k, 4, 1, false, st);
+        else
+            e = launch_stripe_dyn(a, finish, b.sync, plan.waves_k, unit, depth, tuning().stripe_dot2 == 1, st);
     } else if (plan.kernel == W4A16_KERNEL_STRIPE) {
         e = launch_stripe(a, finish, b.sync, plan.waves_k, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE && tile_by_ticket(M, plan.tile_m)) {
-        e = launch_tile_dyn(a, finish, b.sync, plan.waves_k, tuning().tile_depth == 2 ? 2 : 1, st);
+        e = launch_tile_dyn(a, finish, b.sync, plan.waves_k, tuning().tile_depth == 2 && !bf16 ? 2 : 1, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE) {
         e = launch_tile(a, finish, b.sync, plan.tile_m, plan.waves_k, st);
     } else {
         e = launch_wave_split(a, plan.tile_n, st);
     }
-    if (e == hipSuccess && finish == kFinishSecondPass) e = launch_reduce(a.partials, plan.split, M, N, a.Y, st);
+    if (e == hipSuccess && finish == kFinishSecondPass) e = launch_reduce(a.partials, plan.split, M, N, a.Y, bf16, st);
     if (e != hipSuccess) {
         note_hip_error(e);
         if (b.library_acc) {  // what the failed launch left in the accumulator is unknown
@@ -517,6 +524,12 @@ int w4a16_gemm_noalloc(const void *X, const uint32_t *Wpacked, const void *scale
                        int N, int K, void *Y, void *stream, int kernel, int split)
 {
     return run("gemm_noalloc", X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, kFromScratch, nullptr, 0);
+}
+
+int w4a16_gemm_bf16(const void *X, const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int M,
+                    int N, int K, void *Y, void *stream, int kernel, int split)
+{
+    return run("gemm_bf16", X, Wpacked, scales, zeros, group, M, N, K, Y, stream, kernel, split, kFromLibrary, nullptr, 0, true);
 }
 
 int w4a16_set_workspace(void *workspace, size_t workspace_bytes)
@@ -564,7 +577,7 @@ int w4a16_reduce(const float *partials, int S, int M, int N, void *Y, void *stre
     if (!partials || !Y) return W4A16_ERR_NULL;
     if (S < 1 || M < 1 || N < 8 || N % 8 != 0) return W4A16_ERR_SHAPE;
     if (!aligned16(partials) || !aligned16(Y)) return W4A16_ERR_ALIGN;
-    hipError_t e = launch_reduce(partials, S, M, N, static_cast<uint16_t *>(Y), static_cast<hipStream_t>(stream));
+    hipError_t e = launch_reduce(partials, S, M, N, static_cast<uint16_t *>(Y), false, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
     return W4A16_OK;
 }

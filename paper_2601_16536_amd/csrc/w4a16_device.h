@@ -99,4 +99,94 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b)
     return p.u;
 }
 
+// ---- the 16-bit format of A and of the output ----
+//
+// Everything that depends on it sits behind one of two types.  With P the MFMA's sum over a unit of k of
+// (staged x_k) * (operand built from q_k), and xsum = sum_k x_k, the unit's contribution to Eq. 2 is
+//     sum_k x_k s (q_k - z) = (kCodeScale s) P - s (z + kCodeOffset) xsum.
+//
+// FP16 (the paper's format): the operand is the code left in place as a subnormal, q 2^-24 or q 2^-20 with x
+// staged divided by 16 (unpack8 above): kCodeScale = 2^24, kCodeOffset = 0.
+struct ActF16 {
+    static constexpr bool kBF16 = false;
+    static constexpr float kCodeScale = 16777216.0f;
+    static constexpr float kCodeOffset = 0.0f;
+    typedef half8_t operand_t;
+    static __device__ __forceinline__ operand_t unpack(uint32_t w, const Masks &k) { return unpack8(w, k); }
+    static __device__ __forceinline__ uint4_t stage_x(uint4_t d) { return permute_x(d); }
+    static __device__ __forceinline__ float sum_x(uint4_t d) { return sum8(d); }
+    static __device__ __forceinline__ operand_t x_operand(uint4_t d)
+    {
+        H8 v;
+        v.u = d;
+        return v.h;
+    }
+    // the operand against which the staged x sum to sum_k x_k
+    static __device__ __forceinline__ operand_t ones()
+    {
+        return (half8_t){(_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f, (_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f};
+    }
+    static __device__ __forceinline__ float4_t mfma(operand_t x, operand_t b, float4_t c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(x, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_half2(a, b); }
+    static constexpr uint16_t kNaN = 0x7E00u;
+};
+
+// BF16.  A bfloat16 has no room for the subnormal trick (the products with x would be FP32 subnormals), so the
+// operand is 128 + q: the code ORed into the low fraction bits of 128.0 (0x4300, whose unit in the last place is 1).
+// P then carries 128 xsum too much, which the zero-point term takes back: kCodeScale = 1, kCodeOffset = 128.
+// Products of two bfloat16 are exact in FP32; the sum of a unit, about 128 times larger than it needs to be,
+// costs about 7 of FP32's 24 bits, which leaves more than the 8 bits of the output.
+typedef __bf16 bfloat8_t __attribute__((ext_vector_type(8)));
+struct ActBF16 {
+    static constexpr bool kBF16 = true;
+    static constexpr float kCodeScale = 1.0f;
+    static constexpr float kCodeOffset = 128.0f;
+    typedef bfloat8_t operand_t;
+    union B8 {
+        uint4_t u;
+        bfloat8_t b;
+    };
+    // k order 0,4 | 1,5 | 2,6 | 3,7 as in the FP16 form; every code moved to bits 0-3 of its half
+    static __device__ __forceinline__ operand_t unpack(uint32_t w, const Masks &k)
+    {
+        const uint32_t base = 0x43004300u;
+        B8 r;
+        r.u = (uint4_t){(w & k.lo) | base, ((w >> 4) & k.lo) | base, ((w >> 8) & k.lo) | base, ((w >> 12) & k.lo) | base};
+        return r.b;
+    }
+    static __device__ __forceinline__ uint4_t stage_x(uint4_t d)
+    {
+        return (uint4_t){__builtin_amdgcn_perm(d[2], d[0], 0x05040100u), __builtin_amdgcn_perm(d[2], d[0], 0x07060302u),
+                         __builtin_amdgcn_perm(d[3], d[1], 0x05040100u), __builtin_amdgcn_perm(d[3], d[1], 0x07060302u)};
+    }
+    static __device__ __forceinline__ float sum_x(uint4_t d)
+    {
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += __builtin_bit_cast(float, d[e] << 16) + __builtin_bit_cast(float, d[e] & 0xFFFF0000u);
+        return s;
+    }
+    static __device__ __forceinline__ operand_t x_operand(uint4_t d)
+    {
+        B8 v;
+        v.u = d;
+        return v.b;
+    }
+    static __device__ __forceinline__ operand_t ones()
+    {
+        B8 v;
+        v.u = (uint4_t){0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+        return v.b;
+    }
+    static __device__ __forceinline__ float4_t mfma(operand_t x, operand_t b, float4_t c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, b, c, 0, 0, 0); }
+    // round to nearest even (the hardware's v_cvt_pk_bf16_f32)
+    static __device__ __forceinline__ uint32_t pack2(float a, float b)
+    {
+        typedef __bf16 bfloat2_t __attribute__((ext_vector_type(2)));
+        const bfloat2_t p = {(__bf16)a, (__bf16)b};
+        return __builtin_bit_cast(uint32_t, p);
+    }
+    static constexpr uint16_t kNaN = 0x7FC0u;
+};
+
 }  // namespace w4a16

@@ -1,5 +1,5 @@
 // How a workgroup's waves, and then the K slices of different workgroups, meet
-// (Algorithm 1, Phase 3: C = sum_i C_i, then the cast to FP16).  Shared by the
+// (Algorithm 1, Phase 3: C = sum_i C_i, then the cast to the 16-bit output format).  Shared by the
 // STRIPE and TILE families.
 #pragma once
 #include "w4a16_device.h"
@@ -19,7 +19,6 @@ constexpr int kFixMaxSlices = 63;
 constexpr unsigned long long kFixBias = 1ull << 50;
 constexpr unsigned long long kFixPoison = 1ull << 57;
 constexpr unsigned long long kFixOne = 1ull << 58;
-constexpr uint16_t kHalfNaN = 0x7E00u;
 
 // A slice sum that is not NaN.
 __device__ __forceinline__ unsigned long long to_fixed(float v)
@@ -45,13 +44,14 @@ __device__ __forceinline__ float from_fixed(unsigned long long total)
 }
 
 // One slice's sum into the accumulator word of an output; the last of `split` arrivals casts, stores Y and
-// clears the word.  `nan` says the slice sum is NaN (`add` then carries the value 0).
+// clears the word.  `nan` says the slice sum is NaN (`add` then carries the value 0).  Act: the output's format.
+template <typename Act>
 __device__ __forceinline__ void add_slice(unsigned long long *word, unsigned long long add, bool nan, int split, uint16_t *y)
 {
     if (nan) __hip_atomic_fetch_or(word, kFixPoison, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ahead of this slice's add: same thread, same address
     const unsigned long long total = __hip_atomic_fetch_add(word, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
     if ((total >> 58) == (unsigned long long)split) {
-        *y = (total & kFixPoison) ? kHalfNaN : (uint16_t)(pack_half2(from_fixed(total), 0.f) & 0xFFFFu);
+        *y = (total & kFixPoison) ? Act::kNaN : (uint16_t)(Act::pack2(from_fixed(total), 0.f) & 0xFFFFu);
         __hip_atomic_store(word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
@@ -62,7 +62,7 @@ __device__ __forceinline__ void add_slice(unsigned long long *word, unsigned lon
 // the atomic finish wants VW = 1 (consecutive lanes on consecutive outputs, four cache lines per
 // wave-wide atomic), the others VW = 4.  `sync` is the accumulator [M, N] (64-bit words, all zero
 // before the launch and left zero by it).
-template <int ROWS, int COLS, int VW, int MIN_WAVES, typename WriteMine>
+template <typename Act, int ROWS, int COLS, int VW, int MIN_WAVES, typename WriteMine>
 __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int finish, unsigned long long *__restrict__ sync, unsigned char *smem,
                                                   const WriteMine &write_mine, int red_waves, int row0, int col0, int slice)
 {
@@ -106,13 +106,13 @@ __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int f
         const size_t out = (size_t)m * a.N + col;
         if constexpr (VW == 4) {
             if (finish == kFinishDirect)
-                *reinterpret_cast<uint2_t *>(a.Y + out) = (uint2_t){pack_half2(v[k][0], v[k][1]), pack_half2(v[k][2], v[k][3])};
+                *reinterpret_cast<uint2_t *>(a.Y + out) = (uint2_t){Act::pack2(v[k][0], v[k][1]), Act::pack2(v[k][2], v[k][3])};
             else
                 *reinterpret_cast<float4_t *>(a.partials + (size_t)slice * a.M * a.N + out) = v[k];
         } else {
             const float sum = v[k][0];
             const bool nan = sum != sum;
-            add_slice(sync + out, to_fixed(nan ? 0.f : sum), nan, a.split, a.Y + out);
+            add_slice<Act>(sync + out, to_fixed(nan ? 0.f : sum), nan, a.split, a.Y + out);
         }
     }
 }

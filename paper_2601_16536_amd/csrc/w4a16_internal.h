@@ -10,16 +10,17 @@ namespace w4a16 {
 // Arguments every multiply kernel takes (Eq. 2 operands plus the Split-K
 // partition of Algorithm 1, Phase 2).
 struct GemmArgs {
-    const uint16_t *X;        // fp16 [M,K]
+    const uint16_t *X;        // fp16 [M,K], or bfloat16 when bf16 is set
     const uint32_t *Wp;       // [K/8,N]
     const uint16_t *scales;   // fp16 [K/group,N]
     const uint32_t *Zp;       // [K/group,N/8], or null: symmetric quantisation, every zero point is 8
-    uint16_t *Y;              // fp16 [M,N]
+    uint16_t *Y;              // [M,N] in the format of X
     float *partials;          // fp32 [S,M,N] (unused when split == 1)
     int group, M, N, K;
     int split;                // S
     int groups_per_split;
     int groups;               // K / group (kept here so that no kernel divides for it)
+    int bf16;                 // X and Y are bfloat16 (scales stay FP16: they belong to the weights)
 };
 
 
@@ -73,6 +74,6 @@ hipError_t launch_dequant(const uint32_t *Wp, const uint16_t *scales, const uint
 hipError_t launch_quantize(const uint16_t *W16, int group, int N, int K, uint32_t *Wp, uint16_t *scales, uint32_t *Zp,
                            hipStream_t stream);
 // Second pass (Algorithm 1, Phase 3).
-hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream);
+hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, bool bf16, hipStream_t stream);
 
 }  // namespace w4a16

@@ -1,15 +1,16 @@
 // Second pass of Split-K (Algorithm 1, Phase 3): C = sum_{i<S} C_i element by
-// element in FP32, i ascending, then one round-to-nearest-even cast to FP16.
+// element in FP32, i ascending, then one round-to-nearest-even cast to FP16 (or
+// to bfloat16, for bfloat16 activations).
+#include "w4a16_device.h"
 #include "w4a16_internal.h"
 
 namespace w4a16 {
 namespace {
 
-typedef float float4_t __attribute__((ext_vector_type(4)));
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 
 // One thread owns four consecutive columns of one row (N % 8 == 0 keeps the
 // 16-byte loads aligned and inside the row).
+template <typename Act>
 __global__ __launch_bounds__(256) void reduce_kernel(const float *__restrict__ partials, int S, size_t MN,
                                                     uint16_t *__restrict__ Y)
 {
@@ -25,8 +26,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const float *__restrict__ p
         for (int e = 0; e < 8; ++e) acc += v[e];
     }
     for (; s < S; ++s) acc += *reinterpret_cast<const float4_t *>(partials + (size_t)s * MN + i4);
-    half4_t h = {(_Float16)acc[0], (_Float16)acc[1], (_Float16)acc[2], (_Float16)acc[3]};
-    *reinterpret_cast<half4_t *>(Y + i4) = h;
+    *reinterpret_cast<uint2_t *>(Y + i4) = (uint2_t){Act::pack2(acc[0], acc[1]), Act::pack2(acc[2], acc[3])};
 }
 
 // Clears n words of a fixed-point accumulator (a fill kernel, so that a caller may capture it in a HIP graph).
@@ -44,11 +44,14 @@ hipError_t launch_accumulator_clear(unsigned long long *acc, size_t n, hipStream
     return hipGetLastError();
 }
 
-hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, hipStream_t stream)
+hipError_t launch_reduce(const float *partials, int S, int M, int N, uint16_t *Y, bool bf16, hipStream_t stream)
 {
     const size_t MN = (size_t)M * N;
     const unsigned blocks = (unsigned)((MN / 4 + 255) / 256);
-    hipLaunchKernelGGL(reduce_kernel, dim3(blocks), dim3(256), 0, stream, partials, S, MN, Y);
+    if (bf16)
+        hipLaunchKernelGGL(reduce_kernel<ActBF16>, dim3(blocks), dim3(256), 0, stream, partials, S, MN, Y);
+    else
+        hipLaunchKernelGGL(reduce_kernel<ActF16>, dim3(blocks), dim3(256), 0, stream, partials, S, MN, Y);
     return hipGetLastError();
 }
 

@@ -288,9 +288,9 @@ __global__ __launch_bounds__(Mma<MROWS>::kMaxThreads) void stripe_kernel(const G
         for (int i = 0; i < MROWS; ++i) mine[i * 64 + lane] = (float4_t){tot[0][i], tot[1][i], tot[2][i], tot[3][i]};
     };
     if (finish == kFinishAccumulator)
-        reduce_and_finish<MROWS, kStripe, 1, Mma<MROWS>::kMinWaves>(a, finish, sync, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
+        reduce_and_finish<ActF16, MROWS, kStripe, 1, Mma<MROWS>::kMinWaves>(a, finish, sync, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
     else
-        reduce_and_finish<MROWS, kStripe, 4, Mma<MROWS>::kMinWaves>(a, finish, sync, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
+        reduce_and_finish<ActF16, MROWS, kStripe, 4, Mma<MROWS>::kMinWaves>(a, finish, sync, smem, write_mine, red_waves, 0, stripe * kStripe, slice);
 }
 
 int mrows_of(int M) { return M == 1 ? 1 : (M == 2 ? 2 : (M <= 4 ? 4 : (M <= 8 ? 8 : 16))); }
@@ -349,6 +349,7 @@ size_t stripe_lds_bytes(int M, int group, int groups_per_split, int waves)
 hipError_t launch_stripe(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
 {
     if (a.M > 16 || a.group % (8 * kBlockRows) != 0) return hipErrorInvalidValue;
+    if (a.bf16) return hipErrorInvalidValue;  // FP16 activations only (the scheduler never takes this form by itself)
     if (!finish_args_ok(a, finish, sync)) return hipErrorInvalidValue;
     switch (mrows_of(a.M)) {
     case 1: return launch_m<1>(a, finish, sync, waves, stream);

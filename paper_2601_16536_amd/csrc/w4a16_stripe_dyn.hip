@@ -55,7 +55,6 @@ namespace {
 
 constexpr int kStripe = 256;            // columns per workgroup: 64 lanes x 4 words
 constexpr int kLdsLimit = 144 * 1024;
-constexpr float kFix48 = 281474976710656.0f;   // 2^48: P carries 2^-24, the sums are kept in units of 2^-24
 constexpr double kSumMax = 562949953421312.0;   // 2^49 = 2^25 in units of 2^-24: the clamp of a wave's and a workgroup's sum
 constexpr long long kNaNMark = 1ll << 58;       // added to the LDS sum of an output by a wave whose sum is NaN
 
@@ -86,7 +85,7 @@ __host__ __device__ inline Lds lds_layout(int mrows, int rows, int groups)
 // one unit in flight, its successor requested just before the unit is used, so that a wave always has a request out.
 // DOT2: the dot products on the vector ALU (v_dot2_f32_f16, two k per instruction and row of X) instead of the MFMA:
 // the form a wavefront-level FMA design would take, kept for the measurement that decided against it.
-template <int MROWS, int U, int D, bool AHEAD, bool DOT2>
+template <typename Act, int MROWS, int U, int D, bool AHEAD, bool DOT2>
 __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -155,8 +154,8 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
     auto x_put = [&](int e, uint4_t d) {
         if (e >= n_x) return;
         const int row = e / MROWS, m = e % MROWS;
-        *reinterpret_cast<uint4_t *>(smem + L.xs + (uint32_t)e * 16u) = permute_x(d);
-        *reinterpret_cast<float *>(smem + L.xsum + ((uint32_t)m * rows + row) * 4u) = sum8(d);
+        *reinterpret_cast<uint4_t *>(smem + L.xs + (uint32_t)e * 16u) = Act::stage_x(d);
+        *reinterpret_cast<float *>(smem + L.xsum + ((uint32_t)m * rows + row) * 4u) = Act::sum_x(d);
     };
     auto sc_put = [&](int e, uint4_t d) { if (e < n_sc) *reinterpret_cast<uint4_t *>(smem + L.sc + (uint32_t)e * 16u) = d; };
     auto zp_put = [&](int e, uint4_t d) { if (e < n_zp) *reinterpret_cast<uint4_t *>(smem + L.zp + (uint32_t)e * 16u) = d | zfill; };
@@ -228,6 +227,7 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
     auto compute_unit = [&](uint4_t(&b)[U], int row) {
         float4_t part[4];
         if constexpr (DOT2) {
+            static_assert(!DOT2 || !Act::kBF16, "the vector-ALU form exists for FP16 only");
 #pragma unroll
             for (int c = 0; c < 4; ++c) part[c] = zero4;
 #pragma unroll
@@ -253,11 +253,9 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
         } else {
 #pragma unroll
             for (int t = 0; t < U; ++t) {
-                H8 x;
-                x.u = *reinterpret_cast<const uint4_t *>(smem + xa0 + (uint32_t)(row + t) * xstep);
+                const typename Act::operand_t x = Act::x_operand(*reinterpret_cast<const uint4_t *>(smem + xa0 + (uint32_t)(row + t) * xstep));
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    part[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, unpack8(b[t][c], masks), t == 0 ? zero4 : part[c], 0, 0, 0);
+                for (int c = 0; c < 4; ++c) part[c] = Act::mfma(x, Act::unpack(b[t][c], masks), t == 0 ? zero4 : part[c]);
             }
         }
         // the unit is done: scale and zero point (Eq. 2), then the exact sums
@@ -279,8 +277,8 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
         const float s[4] = {(float)s01.h[0], (float)s01.h[1], (float)s23.h[0], (float)s23.h[1]};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const float sp = s[c] * kFix48;                                        // 2^48 s
-            const float sz24 = -s[c] * (float)((zw >> (4 * c)) & 15u) * kFixScale;  // -2^24 s z
+            const float sp = s[c] * (Act::kCodeScale * kFixScale);  // FP16: 2^48 s (P carries 2^-24, the sums are in units of 2^-24)
+            const float sz24 = -s[c] * ((float)((zw >> (4 * c)) & 15u) + Act::kCodeOffset) * kFixScale;  // -2^24 s z
 #pragma unroll
             for (int i = 0; i < MROWS; ++i) {
                 float v = __builtin_fmaf(sp, part[c][i], sz24 * xs[i]);            // the unit's contribution, in units of 2^-24
@@ -356,7 +354,7 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
         const bool nan = fx >= (kNaNMark >> 1);  // sixteen waves' clamped sums stay below 2^53
         const size_t out = (size_t)m * a.N + col;
         if (finish == kFinishAccumulator) {
-            add_slice(sync + out, to_fixed(nan ? 0ll : fx), nan, a.split, a.Y + out);
+            add_slice<Act>(sync + out, to_fixed(nan ? 0ll : fx), nan, a.split, a.Y + out);
 #ifdef W4A16_TIMELINE
             TB = __builtin_amdgcn_s_memrealtime();
 #endif
@@ -364,7 +362,7 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
             constexpr long long lim = 1ll << 49;
             const float v = nan ? __builtin_nanf("") : (float)((double)(fx < -lim ? -lim : (fx > lim ? lim : fx)) * (1.0 / 16777216.0));
             if (finish == kFinishDirect)
-                a.Y[out] = nan ? kHalfNaN : (uint16_t)(pack_half2(v, 0.f) & 0xFFFFu);
+                a.Y[out] = nan ? Act::kNaN : (uint16_t)(Act::pack2(v, 0.f) & 0xFFFFu);
             else
                 a.partials[(size_t)slice * a.M * a.N + out] = v;
         }
@@ -381,18 +379,18 @@ __global__ __launch_bounds__(1024) void stripe_dyn_kernel(const GemmArgs a, cons
 
 int mrows_of(int M) { return M == 1 ? 1 : (M == 2 ? 2 : 4); }
 
-template <int MROWS, int U, int D, bool AHEAD, bool DOT2>
+template <typename Act, int MROWS, int U, int D, bool AHEAD, bool DOT2>
 hipError_t launch_m(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
 {
     const size_t lds = stripe_dyn_lds_bytes(a.M, a.group, a.groups_per_split);
     if (lds > (size_t)kLdsLimit) return hipErrorInvalidValue;
     const int nstripes = (a.N + kStripe - 1) / kStripe;
     if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_dyn_kernel<MROWS, U, D, AHEAD, DOT2>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_dyn_kernel<Act, MROWS, U, D, AHEAD, DOT2>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((stripe_dyn_kernel<MROWS, U, D, AHEAD, DOT2>), dim3(a.split, nstripes), dim3(waves * 64), lds, stream, a, finish, sync);
+    hipLaunchKernelGGL((stripe_dyn_kernel<Act, MROWS, U, D, AHEAD, DOT2>), dim3(a.split, nstripes), dim3(waves * 64), lds, stream, a, finish, sync);
     return hipGetLastError();
 }
 
@@ -417,8 +415,8 @@ hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *
     if ((a.N + kStripe - 1) / kStripe > 65535) return hipErrorInvalidValue;  // stripes are the grid's y
     // depth 0 = one unit in flight, its successor requested ahead of its use
 #define W4A16_DYN_CASE(MR, UU, DD, DOT) \
-    if (mrows_of(a.M) == MR && unit_rows == UU && depth == DD && dot2 == DOT) \
-        return launch_m<MR, UU, (DD ? DD : 2), DD == 0, DOT>(a, finish, sync, waves, stream);
+    if (mrows_of(a.M) == MR && unit_rows == UU && depth == DD && dot2 == DOT && !a.bf16) \
+        return launch_m<ActF16, MR, UU, (DD ? DD : 2), DD == 0, DOT>(a, finish, sync, waves, stream);
 #define W4A16_DYN_M(UU, DD, DOT) W4A16_DYN_CASE(1, UU, DD, DOT) W4A16_DYN_CASE(2, UU, DD, DOT) W4A16_DYN_CASE(4, UU, DD, DOT)
     W4A16_DYN_M(4, 1, false)  // the scheduler's choice
     W4A16_DYN_M(2, 1, false)  // the rest: for sweeps
@@ -427,6 +425,11 @@ hipError_t launch_stripe_dyn(const GemmArgs &a, int finish, unsigned long long *
     W4A16_DYN_M(8, 1, false)
     W4A16_DYN_M(4, 0, false)
     W4A16_DYN_M(4, 1, true)
+    if (a.bf16 && unit_rows == 4 && depth == 1 && !dot2) {  // bfloat16 activations: the scheduler's choice only
+        if (mrows_of(a.M) == 1) return launch_m<ActBF16, 1, 4, 1, false, false>(a, finish, sync, waves, stream);
+        if (mrows_of(a.M) == 2) return launch_m<ActBF16, 2, 4, 1, false, false>(a, finish, sync, waves, stream);
+        return launch_m<ActBF16, 4, 4, 1, false, false>(a, finish, sync, waves, stream);
+    }
 #undef W4A16_DYN_M
 #undef W4A16_DYN_CASE
     return hipErrorInvalidValue;

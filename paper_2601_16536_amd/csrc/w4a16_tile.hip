@@ -53,7 +53,7 @@ struct Shape {
     static constexpr int kOutBytes = kRowsX * kTileCols * 4;     // a wave's result tile in fp32
 };
 
-template <int RT>
+template <typename Act, int RT>
 __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync, const int row_blocks, const int red_waves)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int f
     auto x_store = [&](const uint4_t(&d)[Sh::kPerLane], int par) {
 #pragma unroll
         for (int q = 0; q < Sh::kPerLane; ++q)
-            *reinterpret_cast<uint4_t *>(wl + par * Sh::kBufBytes + xl[q]) = permute_x(d[q]);
+            *reinterpret_cast<uint4_t *>(wl + par * Sh::kBufBytes + xl[q]) = Act::stage_x(d[q]);
     };
 
     // X of the first chunk goes ahead of the weights: loads return in order, and X (mostly cache hits) must
@@ -185,8 +185,8 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int f
         xsum[rt] = (float4_t){0.f, 0.f, 0.f, 0.f};
     }
     const Masks masks = make_masks();
-    // sum_k x_k over a block comes from the MFMA too: X against ones (16 where the staged x was divided by 16)
-    const half8_t ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f, (_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f};
+    // sum_k x_k over a block comes from the MFMA too: X against ones (FP16: 16 where the staged x was divided by 16)
+    const typename Act::operand_t ones = Act::ones();
     uint32_t gnext = (wb0 / bpg + 1) * bpg;  // first block of the group after the current one
 
     // Only this wave touches its LDS and the LDS operations of one wave complete in order; the
@@ -205,17 +205,15 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int f
                 // that reloading their registers below needs no wait on younger loads.
                 asm volatile("" ::"v"(buf[p].sc[0]), "v"(buf[p].sc[1]), "v"(buf[p].zw));
                 const unsigned char *xb = smem + xa0 + cpar * Sh::kBufBytes + lb * (kBlockRows * Sh::kRowStride * 16);
-                half8_t bop[4];
+                typename Act::operand_t bop[4];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) bop[c] = unpack8(buf[p].w[c], masks);
+                for (int c = 0; c < 4; ++c) bop[c] = Act::unpack(buf[p].w[c], masks);
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) {
-                    H8 x;
-                    x.u = *reinterpret_cast<const uint4_t *>(xb + rt * 256);
+                    const typename Act::operand_t x = Act::x_operand(*reinterpret_cast<const uint4_t *>(xb + rt * 256));
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        part[rt][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, bop[c], part[rt][c], 0, 0, 0);
-                    xsum[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, ones, xsum[rt], 0, 0, 0);
+                    for (int c = 0; c < 4; ++c) part[rt][c] = Act::mfma(x, bop[c], part[rt][c]);
+                    xsum[rt] = Act::mfma(x, ones, xsum[rt]);
                 }
                 if (cur + 1 == gnext || cur + 1 == wb1) {
                     // the wave's rows of this group are done: scale and zero point (Eq. 2)
@@ -226,8 +224,8 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int f
                     const uint32_t zw = buf[p].zw >> zsh;
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
-                        const float sp = s[c] * 16777216.0f;                       // 2^24 s
-                        const float sz = -s[c] * (float)((zw >> (4 * c)) & 15u);   // -s z
+                        const float sp = s[c] * Act::kCodeScale;                                          // FP16: 2^24 s
+                        const float sz = -s[c] * ((float)((zw >> (4 * c)) & 15u) + Act::kCodeOffset);   // -s z
 #pragma unroll
                         for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
@@ -260,9 +258,9 @@ __global__ __launch_bounds__(512) void tile_kernel(const GemmArgs a, const int f
                 mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = (float4_t){tot[rt][0][i], tot[rt][1][i], tot[rt][2][i], tot[rt][3][i]};
     };
     if (finish == kFinishAccumulator)
-        reduce_and_finish<Sh::kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+        reduce_and_finish<Act, Sh::kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
     else
-        reduce_and_finish<Sh::kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+        reduce_and_finish<Act, Sh::kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
 }
 
 // ---- group = 128: the waves' runs are whole quantisation groups ----
@@ -288,7 +286,7 @@ struct GroupShape {
     static constexpr int kOutBytes = kRowsX * kTileCols * 4;
 };
 
-template <int RT>
+template <typename Act, int RT>
 __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync, const int row_blocks, const int red_waves)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -381,7 +379,7 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
     auto x_store = [&](int par) {
 #pragma unroll
         for (int q = 0; q < Sh::kPerLane; ++q)
-            *reinterpret_cast<uint4_t *>(wl + par * Sh::kBufBytes + xl0 + (kWholeGroup ? 4 * q : 16 * q) * 16) = permute_x(xd[q]);
+            *reinterpret_cast<uint4_t *>(wl + par * Sh::kBufBytes + xl0 + (kWholeGroup ? 4 * q : 16 * q) * 16) = Act::stage_x(xd[q]);
     };
 
     float4_t tot[RT][4];
@@ -405,8 +403,8 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
 
         const uint32_t xa0 = (uint32_t)(wave * Sh::kWaveBytes + (g4 * Sh::kRowStride + j) * 16);  // A entry of block 0, row tile 0
         const Masks masks = make_masks();
-        // sum_k x_k over a group comes from the MFMA too: X against ones (16 where the staged x was divided by 16)
-        const half8_t ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f, (_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f};
+        // sum_k x_k over a group comes from the MFMA too: X against ones (FP16: 16 where the staged x was divided by 16)
+        const typename Act::operand_t ones = Act::ones();
         const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
 
         // One group: its four blocks from ring place R, chunk buffers by parity of the chunk number.  Only this
@@ -428,17 +426,15 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
                 const int c = p / CB, lb = p % CB;
                 const int par = (H * Sh::kChunks + c) & 1;
                 const unsigned char *xb = smem + xa0 + par * Sh::kBufBytes + lb * (kBlockRows * Sh::kRowStride * 16);
-                half8_t bop[4];
+                typename Act::operand_t bop[4];
 #pragma unroll
-                for (int cc = 0; cc < 4; ++cc) bop[cc] = unpack8(wq[R * kBpg + p][cc], masks);
+                for (int cc = 0; cc < 4; ++cc) bop[cc] = Act::unpack(wq[R * kBpg + p][cc], masks);
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) {
-                    H8 x;
-                    x.u = *reinterpret_cast<const uint4_t *>(xb + rt * 256);
+                    const typename Act::operand_t x = Act::x_operand(*reinterpret_cast<const uint4_t *>(xb + rt * 256));
 #pragma unroll
-                    for (int cc = 0; cc < 4; ++cc)
-                        part[rt][cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, bop[cc], p == 0 ? zero4 : part[rt][cc], 0, 0, 0);
-                    xsum[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, ones, p == 0 ? zero4 : xsum[rt], 0, 0, 0);
+                    for (int cc = 0; cc < 4; ++cc) part[rt][cc] = Act::mfma(x, bop[cc], p == 0 ? zero4 : part[rt][cc]);
+                    xsum[rt] = Act::mfma(x, ones, p == 0 ? zero4 : xsum[rt]);
                 }
                 if (lb == CB - 1) {
                     // The chunk is done.  Its successor's X, asked for a chunk ago, goes to the other buffer, and
@@ -462,8 +458,8 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
             const uint32_t z = zw >> zsh;
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
-                const float sp = s[cc] * 16777216.0f;                      // 2^24 s
-                const float sz = -s[cc] * (float)((z >> (4 * cc)) & 15u);  // -s z
+                const float sp = s[cc] * Act::kCodeScale;                                         // FP16: 2^24 s
+                const float sz = -s[cc] * ((float)((z >> (4 * cc)) & 15u) + Act::kCodeOffset);  // -s z
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -498,9 +494,9 @@ __global__ __launch_bounds__(512) void tile_group_kernel(const GemmArgs a, const
             for (int i = 0; i < 4; ++i) mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = mine4[rt][i];
     };
     if (finish == kFinishAccumulator)
-        reduce_and_finish<Sh::kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+        reduce_and_finish<Act, Sh::kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
     else
-        reduce_and_finish<Sh::kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+        reduce_and_finish<Act, Sh::kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
 }
 
 // The waves' chunk buffers; the final sums reuse the space, a whole number of waves' tiles per round.
@@ -553,6 +549,19 @@ hipError_t launch_kernel(Kernel kernel, const Launch &l, const GemmArgs &a, int 
     return hipGetLastError();
 }
 
+template <typename Act>
+hipError_t launch_rows(const Launch &l, const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, int waves, int loop, hipStream_t stream)
+{
+    if (loop == kLoopGroups) {
+        if (rows_x == 16) return launch_kernel(&tile_group_kernel<Act, 1>, l, a, finish, sync, waves, stream);
+        if (rows_x == 32) return launch_kernel(&tile_group_kernel<Act, 2>, l, a, finish, sync, waves, stream);
+        return launch_kernel(&tile_group_kernel<Act, 4>, l, a, finish, sync, waves, stream);
+    }
+    if (rows_x == 16) return launch_kernel(&tile_kernel<Act, 1>, l, a, finish, sync, waves, stream);
+    if (rows_x == 32) return launch_kernel(&tile_kernel<Act, 2>, l, a, finish, sync, waves, stream);
+    return launch_kernel(&tile_kernel<Act, 4>, l, a, finish, sync, waves, stream);
+}
+
 }  // namespace
 
 hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, int waves, hipStream_t stream)
@@ -563,14 +572,8 @@ hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, 
     const int loop = a.group == 128 ? kLoopGroups : kLoopBlocks;  // the loop over single blocks: 0.5-0.7 us slower on small shapes, equal on large
     Launch l;
     if (!prepare(a, rows_x, waves, loop, &l)) return hipErrorInvalidValue;
-    if (loop == kLoopGroups) {
-        if (rows_x == 16) return launch_kernel(&tile_group_kernel<1>, l, a, finish, sync, waves, stream);
-        if (rows_x == 32) return launch_kernel(&tile_group_kernel<2>, l, a, finish, sync, waves, stream);
-        return launch_kernel(&tile_group_kernel<4>, l, a, finish, sync, waves, stream);
-    }
-    if (rows_x == 16) return launch_kernel(&tile_kernel<1>, l, a, finish, sync, waves, stream);
-    if (rows_x == 32) return launch_kernel(&tile_kernel<2>, l, a, finish, sync, waves, stream);
-    return launch_kernel(&tile_kernel<4>, l, a, finish, sync, waves, stream);
+    if (a.bf16) return launch_rows<ActBF16>(l, a, finish, sync, rows_x, waves, loop, stream);
+    return launch_rows<ActF16>(l, a, finish, sync, rows_x, waves, loop, stream);
 }
 
 }  // namespace w4a16

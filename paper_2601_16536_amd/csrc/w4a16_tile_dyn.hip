@@ -25,7 +25,6 @@ constexpr int kTileCols = 64;
 constexpr int kRowsX = 16;
 constexpr int kBlockRows = 4;                    // packed rows per block: one MFMA step of 32 k
 constexpr int kRowStride = kRowsX + 1;           // LDS entries per packed row (padded: conflict-free writes and reads)
-constexpr float kFix48 = 281474976710656.0f;     // 2^48: P carries 2^-24, the sums are kept in units of 2^-24
 constexpr double kSumMax = 562949953421312.0;    // 2^49 = 2^25 in units of 2^-24: the clamp of a wave's sum
 constexpr long long kNaNMark = 1ll << 58;        // added to the LDS sum of an output by a wave whose sum is NaN
 
@@ -35,7 +34,7 @@ constexpr uint32_t kLdsX = kLdsAcc + kRowsX * kTileCols * 8;
 template <int UB>
 constexpr uint32_t unit_x_bytes() { return UB * kBlockRows * kRowStride * 16; }
 
-template <int UB, int D>
+template <typename Act, int UB, int D>
 __global__ __launch_bounds__(1024) void tile_dyn_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -122,8 +121,8 @@ __global__ __launch_bounds__(1024) void tile_dyn_kernel(const GemmArgs a, const 
 #pragma unroll
         for (int i = 0; i < 4; ++i) tot[c][i] = 0.0;
     const Masks masks = make_masks();
-    // sum_k x_k over a unit comes from the MFMA too: X against ones (16 where the staged x was divided by 16)
-    const half8_t ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f, (_Float16)1.f, (_Float16)1.f, (_Float16)16.f, (_Float16)16.f};
+    // sum_k x_k over a unit comes from the MFMA too: X against ones (FP16: 16 where the staged x was divided by 16)
+    const typename Act::operand_t ones = Act::ones();
     const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
 
     auto draw = [&]() -> int {
@@ -139,17 +138,15 @@ __global__ __launch_bounds__(1024) void tile_dyn_kernel(const GemmArgs a, const 
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
         for (int q = 0; q < UB; ++q)
-            *reinterpret_cast<uint4_t *>(myx + (uint32_t)q * (kBlockRows * kRowStride * 16) + xl) = permute_x(r.x[q]);
+            *reinterpret_cast<uint4_t *>(myx + (uint32_t)q * (kBlockRows * kRowStride * 16) + xl) = Act::stage_x(r.x[q]);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         float4_t part[4], xsum;
 #pragma unroll
         for (int q = 0; q < UB; ++q) {
-            H8 x;
-            x.u = *reinterpret_cast<const uint4_t *>(myx + (uint32_t)q * (kBlockRows * kRowStride * 16) + xa);
+            const typename Act::operand_t x = Act::x_operand(*reinterpret_cast<const uint4_t *>(myx + (uint32_t)q * (kBlockRows * kRowStride * 16) + xa));
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                part[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, unpack8(r.w[q][c], masks), q == 0 ? zero4 : part[c], 0, 0, 0);
-            xsum = __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, ones, q == 0 ? zero4 : xsum, 0, 0, 0);
+            for (int c = 0; c < 4; ++c) part[c] = Act::mfma(x, Act::unpack(r.w[q][c], masks), q == 0 ? zero4 : part[c]);
+            xsum = Act::mfma(x, ones, q == 0 ? zero4 : xsum);
         }
         // the unit is done: scale and zero point (Eq. 2), then the exact sums
         H2 s01, s23;
@@ -159,8 +156,8 @@ __global__ __launch_bounds__(1024) void tile_dyn_kernel(const GemmArgs a, const 
         const uint32_t zw = r.zw >> zsh;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const float sp = s[c] * kFix48;                                        // 2^48 s
-            const float sz24 = -s[c] * (float)((zw >> (4 * c)) & 15u) * kFixScale;  // -2^24 s z
+            const float sp = s[c] * (Act::kCodeScale * kFixScale);  // FP16: 2^48 s (P carries 2^-24, the sums are in units of 2^-24)
+            const float sz24 = -s[c] * ((float)((zw >> (4 * c)) & 15u) + Act::kCodeOffset) * kFixScale;  // -2^24 s z
 #pragma unroll
             for (int i = 0; i < 4; ++i)  // exact from here on: integers, the sum below 2^53 (an infinity or a NaN stays one)
                 tot[c][i] += (double)__builtin_rintf(__builtin_fmaf(sp, part[c][i], sz24 * xsum[i]));
@@ -202,29 +199,29 @@ __global__ __launch_bounds__(1024) void tile_dyn_kernel(const GemmArgs a, const 
         const bool nan = fx >= (kNaNMark >> 1);  // sixteen waves' clamped sums stay below 2^53
         const size_t out = (size_t)m * a.N + col;
         if (finish == kFinishAccumulator) {
-            add_slice(sync + out, to_fixed(nan ? 0ll : fx), nan, a.split, a.Y + out);
+            add_slice<Act>(sync + out, to_fixed(nan ? 0ll : fx), nan, a.split, a.Y + out);
         } else {
             constexpr long long lim = 1ll << 49;
             const float v = nan ? __builtin_nanf("") : (float)((double)(fx < -lim ? -lim : (fx > lim ? lim : fx)) * (1.0 / 16777216.0));
             if (finish == kFinishDirect)
-                a.Y[out] = nan ? kHalfNaN : (uint16_t)(pack_half2(v, 0.f) & 0xFFFFu);
+                a.Y[out] = nan ? Act::kNaN : (uint16_t)(Act::pack2(v, 0.f) & 0xFFFFu);
             else
                 a.partials[(size_t)slice * a.M * a.N + out] = v;
         }
     }
 }
 
-template <int UB, int D>
+template <typename Act, int UB, int D>
 hipError_t launch_ud(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
 {
     const size_t lds = kLdsX + (size_t)waves * unit_x_bytes<UB>();
     const int ntiles = (a.N + kTileCols - 1) / kTileCols, row_blocks = (a.M + kRowsX - 1) / kRowsX;
     if (ntiles > 65535 || row_blocks > 65535) return hipErrorInvalidValue;
     if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_dyn_kernel<UB, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_dyn_kernel<Act, UB, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((tile_dyn_kernel<UB, D>), dim3(a.split, ntiles, row_blocks), dim3(waves * 64), lds, stream, a, finish, sync);
+    hipLaunchKernelGGL((tile_dyn_kernel<Act, UB, D>), dim3(a.split, ntiles, row_blocks), dim3(waves * 64), lds, stream, a, finish, sync);
     return hipGetLastError();
 }
 
@@ -241,14 +238,20 @@ hipError_t launch_tile_dyn(const GemmArgs &a, int finish, unsigned long long *sy
     if ((unsigned long long)a.M * a.K * 2ull >= 0x7F000000ull) return hipErrorInvalidValue;
     const int bpg = a.group / 32;
     const int ub = bpg % 4 == 0 ? 4 : (bpg % 2 == 0 ? 2 : 1);  // blocks per unit: a unit never crosses a quantisation group
-    if (depth == 2) {
-        if (ub == 4) return launch_ud<4, 2>(a, finish, sync, waves, stream);
-        if (ub == 2) return launch_ud<2, 2>(a, finish, sync, waves, stream);
-        return launch_ud<1, 2>(a, finish, sync, waves, stream);
+    if (a.bf16) {  // bfloat16 activations: the scheduler's depth only
+        if (depth != 1) return hipErrorInvalidValue;
+        if (ub == 4) return launch_ud<ActBF16, 4, 1>(a, finish, sync, waves, stream);
+        if (ub == 2) return launch_ud<ActBF16, 2, 1>(a, finish, sync, waves, stream);
+        return launch_ud<ActBF16, 1, 1>(a, finish, sync, waves, stream);
     }
-    if (ub == 4) return launch_ud<4, 1>(a, finish, sync, waves, stream);
-    if (ub == 2) return launch_ud<2, 1>(a, finish, sync, waves, stream);
-    return launch_ud<1, 1>(a, finish, sync, waves, stream);
+    if (depth == 2) {
+        if (ub == 4) return launch_ud<ActF16, 4, 2>(a, finish, sync, waves, stream);
+        if (ub == 2) return launch_ud<ActF16, 2, 2>(a, finish, sync, waves, stream);
+        return launch_ud<ActF16, 1, 2>(a, finish, sync, waves, stream);
+    }
+    if (ub == 4) return launch_ud<ActF16, 4, 1>(a, finish, sync, waves, stream);
+    if (ub == 2) return launch_ud<ActF16, 2, 1>(a, finish, sync, waves, stream);
+    return launch_ud<ActF16, 1, 1>(a, finish, sync, waves, stream);
 }
 
 }  // namespace w4a16

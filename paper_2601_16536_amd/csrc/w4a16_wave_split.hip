@@ -316,6 +316,7 @@ hipError_t launch_rows(const GemmArgs &a, hipStream_t stream, dim3 grid)
 hipError_t launch_wave_split(const GemmArgs &a, int tile_n, hipStream_t stream)
 {
     if (a.M > 4 || (tile_n != 32 && tile_n != 64)) return hipErrorInvalidValue;
+    if (a.bf16) return hipErrorInvalidValue;  // FP16 activations only (the scheduler never takes this family by itself)
     const dim3 grid(a.split, (a.N + tile_n - 1) / tile_n, 1);
     if (tile_n == 64) {
         if (a.M == 1) return launch_rows<1, 4>(a, stream, grid);
