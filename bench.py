@@ -57,10 +57,10 @@ def log(*a):
 
 
 def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, warm=False, host=None, graph=True,
-              replays=5):
+              replays=5, bf16=False):
     """Returns dict with µs per GEMM: HIP events around `steps` back-to-back GEMMs (one replay of a HIP graph
     that holds them; the median of `replays` replays is the value, the fastest is reported beside it;
-    graph=False times the eager Python loop instead)."""
+    graph=False times the eager Python loop instead).  bf16: the same draw of X as bfloat16, through w4a16_gemm_bf16."""
     cfg = wl.config(name)
     if host is None:
         host = wl.make_config(name)
@@ -68,15 +68,20 @@ def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, wa
     X = np.ascontiguousarray(Xall[:M])
     wbytes = Wp.nbytes + s.nbytes + Zp.nbytes
     copies = 1 if warm else max(2, -(-COLD_BYTES // wbytes))
-    dX = torch.from_numpy(X).cuda()
+    if bf16:
+        Xb = wl.make_x_bf16(max(cfg.Ms), cfg.K, cfg.index, cfg.outliers)[:M]
+        dX = torch.from_numpy(np.ascontiguousarray(Xb).view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        dX = torch.from_numpy(X).cuda()
     base = binding.to_device(X, Wp, s, Zp)[1:]
     sets = [base] + [tuple(t.clone() for t in base) for _ in range(copies - 1)]
-    Y = torch.empty((M, cfg.N), dtype=torch.float16, device="cuda")
+    Y = torch.empty((M, cfg.N), dtype=torch.bfloat16 if bf16 else torch.float16, device="cuda")
     stream = torch.cuda.current_stream()
+    gemm = binding.gemm_bf16 if bf16 else binding.gemm_ex
 
     def call(i):
         W_, S_, Z_ = sets[i % copies]
-        binding.gemm_ex(dX, W_, S_, Z_, cfg.group, kernel=kernel, split=split, out=Y, stream=torch.cuda.current_stream())
+        gemm(dX, W_, S_, Z_, cfg.group, kernel=kernel, split=split, out=Y, stream=torch.cuda.current_stream())
 
     for i in range(warmup):
         call(i)
@@ -415,6 +420,8 @@ def main():
                 r, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), host=h)
                 r2, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), warm=True, host=h)
                 r["us_per_gemm_warm"] = r2["us_per_gemm"]
+                r3, _, _ = time_gemm(torch, binding, wl, name, M, steps, max(10, steps // 10), host=h, bf16=True)
+                r["us_per_gemm_bf16"] = r3["us_per_gemm"]
                 log(json.dumps(r))
                 rows.append(r)
             del h
