@@ -61,15 +61,17 @@ __device__ __forceinline__ void add_slice(unsigned long long *word, unsigned lon
 // groups), then the workgroup's finish.  A thread owns groups of VW neighbouring columns of one row;
 // the atomic finish wants VW = 1 (consecutive lanes on consecutive outputs, four cache lines per
 // wave-wide atomic), the others VW = 4.  `sync` is the accumulator [M, N] (64-bit words, all zero
-// before the launch and left zero by it).
+// before the launch and left zero by it).  `team_waves`: the first so many waves of the workgroup hold results and
+// call this (0 = all of them); the others call reduce_barriers instead, which takes part in the same barriers.
 template <typename Act, int ROWS, int COLS, int VW, int MIN_WAVES, typename WriteMine>
 __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int finish, unsigned long long *__restrict__ sync, unsigned char *smem,
-                                                  const WriteMine &write_mine, int red_waves, int row0, int col0, int slice)
+                                                  const WriteMine &write_mine, int red_waves, int row0, int col0, int slice, int team_waves = 0)
 {
     typedef float vec_t __attribute__((ext_vector_type(VW)));
     constexpr int kGroups = ROWS * COLS / VW;
     constexpr int kOwn = (kGroups + 64 * MIN_WAVES - 1) / (64 * MIN_WAVES);  // groups per thread, at most
-    const int tid = threadIdx.x, wave = tid >> 6, waves = blockDim.x >> 6;
+    const int tid = threadIdx.x, wave = tid >> 6, waves = team_waves ? team_waves : (int)(blockDim.x >> 6);
+    const int nthreads = waves * 64;
     vec_t v[kOwn];
 #pragma unroll
     for (int k = 0; k < kOwn; ++k) v[k] = vec_t(0.f);
@@ -82,8 +84,8 @@ __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int f
         const int nw = waves - w0 < red_waves ? waves - w0 : red_waves;
 #pragma unroll
         for (int k = 0; k < kOwn; ++k) {
-            if (k * (int)blockDim.x >= kGroups) continue;  // uniform: no thread owns a k-th group
-            const int o = tid + k * (int)blockDim.x;
+            if (k * nthreads >= kGroups) continue;  // uniform: no thread owns a k-th group
+            const int o = tid + k * nthreads;
             const int oc = o < kGroups ? o : 0;  // threads past the last group read group 0 and store nothing
             // four reads in flight at a time (past the last wave the last one is read again and not added)
             for (int w = 0; w < nw; w += 4) {
@@ -100,7 +102,7 @@ __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int f
     }
 #pragma unroll
     for (int k = 0; k < kOwn; ++k) {
-        const int o = tid + k * (int)blockDim.x;
+        const int o = tid + k * nthreads;
         const int m = row0 + o / (COLS / VW), col = col0 + VW * (o % (COLS / VW));
         if (o >= kGroups || m >= a.M || col >= a.N) continue;
         const size_t out = (size_t)m * a.N + col;
@@ -114,6 +116,15 @@ __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int f
             const bool nan = sum != sum;
             add_slice<Act>(sync + out, to_fixed(nan ? 0.f : sum), nan, a.split, a.Y + out);
         }
+    }
+}
+
+// The barriers of reduce_and_finish, for the waves of the workgroup that hold no results.
+__device__ __forceinline__ void reduce_barriers(int team_waves, int red_waves)
+{
+    for (int w0 = 0; w0 < team_waves; w0 += red_waves) {
+        __syncthreads();
+        __syncthreads();
     }
 }
 

@@ -89,18 +89,59 @@ def test_small_shapes_every_split(gpu, M, K, N, group):
             assert r <= 1.0, (M, K, N, group, kernel, split, r)
 
 
+@pytest.mark.parametrize("deq", [1, 2])
 @pytest.mark.parametrize("rows_x", [16, 32, 64])
-def test_tile_family_every_row_block(gpu, rows_x):
-    """The TILE kernels for 16, 32 and 64 rows of X per workgroup.  The scheduler takes the larger blocks
-    only where N is large, so the library's tuning knob forces them here on small ragged shapes
+def test_tile_family_every_row_block(gpu, rows_x, deq):
+    """The TILE kernels for 16, 32 and 64 rows of X per workgroup, in both forms (exact codes as MFMA operands;
+    group = 128 only: weights dequantized to FP16 in registers).  The scheduler takes the larger blocks
+    only where N is large, so the library's tuning knobs force them here on small ragged shapes
     (rows past M, columns past N, fewer groups than waves, group sizes with and without the
     group-aligned loop)."""
     _, binding = gpu
     binding.tune("tile_rows", rows_x)
+    binding.tune("tile_deq", deq)
+    binding.tune("tile_dyn", 2)  # not the ticket form, which 16 rows would take
     try:
         _tile_rows_cases(gpu, rows_x)
     finally:
         binding.tune("tile_rows", 0)
+        binding.tune("tile_deq", 0)
+        binding.tune("tile_dyn", 0)
+
+
+def test_dequantized_operand_form_is_exact_where_fp16_holds_the_weights(gpu):
+    """The many-row TILE form rounds s (q - z) to FP16 once (Algorithm 1, Phase 1).  With power-of-two scales that
+    rounding is exact, and with small integers in X so is every sum: the result must be the oracle's, bit for bit;
+    with one-hot rows of X the result is the FP16 rounding of the weight row itself."""
+    torch, binding = gpu
+    rng = np.random.default_rng(23)
+    M, K, N, group = 70, 1024, 264, 128
+    G = K // group
+    _, Wp, _, Zp = wl.make(1, K, N, index=2300, group=group)
+    s = (2.0 ** rng.integers(-8, -3, (G, N))).astype(np.float16)
+    X = rng.integers(-3, 4, (M, K)).astype(np.float16)
+    ref = orc.gemm(X, Wp, s, Zp, group)
+    binding.tune("tile_deq", 1)
+    binding.tune("tile_dyn", 2)
+    try:
+        for rows_x in (16, 32, 64):
+            binding.tune("tile_rows", rows_x)
+            for split in (1, 3):
+                say("deq exact", rows_x, split)
+                Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=binding.KERNEL_TILE, split=split)
+                assert np.array_equal(Y, orc.to_fp16(ref)), (rows_x, split)
+        X1, Wp1, s1, Zp1 = wl.make(64, K, N, index=2301, group=group)
+        X1[:] = 0
+        ks = rng.choice(K, size=64, replace=False)
+        X1[np.arange(64), ks] = 1
+        say("deq one-hot")
+        binding.tune("tile_rows", 64)
+        Y = run_gpu(gpu, X1, Wp1, s1, Zp1, group, kernel=binding.KERNEL_TILE, split=1)
+        assert np.array_equal(Y, orc.dequant(Wp1, s1, Zp1, group)[ks].astype(np.float16))
+    finally:
+        binding.tune("tile_rows", 0)
+        binding.tune("tile_deq", 0)
+        binding.tune("tile_dyn", 0)
 
 
 def _tile_rows_cases(gpu, rows_x):
