@@ -61,17 +61,16 @@ __device__ __forceinline__ void add_slice(unsigned long long *word, unsigned lon
 // groups), then the workgroup's finish.  A thread owns groups of VW neighbouring columns of one row;
 // the atomic finish wants VW = 1 (consecutive lanes on consecutive outputs, four cache lines per
 // wave-wide atomic), the others VW = 4.  `sync` is the accumulator [M, N] (64-bit words, all zero
-// before the launch and left zero by it).  `team_waves`: the first so many waves of the workgroup hold results and
-// call this (0 = all of them); the others call reduce_barriers instead, which takes part in the same barriers.
+// before the launch and left zero by it).
 template <typename Act, int ROWS, int COLS, int VW, int MIN_WAVES, typename WriteMine>
 __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int finish, unsigned long long *__restrict__ sync, unsigned char *smem,
-                                                  const WriteMine &write_mine, int red_waves, int row0, int col0, int slice, int team_waves = 0)
+                                                  const WriteMine &write_mine, int red_waves, int row0, int col0, int slice)
 {
     typedef float vec_t __attribute__((ext_vector_type(VW)));
     constexpr int kGroups = ROWS * COLS / VW;
     constexpr int kOwn = (kGroups + 64 * MIN_WAVES - 1) / (64 * MIN_WAVES);  // groups per thread, at most
-    const int tid = threadIdx.x, wave = tid >> 6, waves = team_waves ? team_waves : (int)(blockDim.x >> 6);
-    const int nthreads = waves * 64;
+    const int tid = threadIdx.x, wave = tid >> 6, waves = blockDim.x >> 6;
+    const int nthreads = (int)blockDim.x;
     vec_t v[kOwn];
 #pragma unroll
     for (int k = 0; k < kOwn; ++k) v[k] = vec_t(0.f);
@@ -116,15 +115,6 @@ __device__ __forceinline__ void reduce_and_finish(const GemmArgs &a, const int f
             const bool nan = sum != sum;
             add_slice<Act>(sync + out, to_fixed(nan ? 0.f : sum), nan, a.split, a.Y + out);
         }
-    }
-}
-
-// The barriers of reduce_and_finish, for the waves of the workgroup that hold no results.
-__device__ __forceinline__ void reduce_barriers(int team_waves, int red_waves)
-{
-    for (int w0 = 0; w0 < team_waves; w0 += red_waves) {
-        __syncthreads();
-        __syncthreads();
     }
 }
 
