@@ -37,6 +37,18 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 KERNEL_NAMES = {0: "wave_split_kernel", 3: "stripe_kernel", 4: "tile_kernel"}
 
 
+def kernel_name(plan, M, group):
+    """The multiply kernel a plan launches (as rocprofv3 names it, without template arguments)."""
+    if plan["kernel"] == 3:
+        return "stripe_dyn_kernel" if M <= 4 else "stripe_kernel"
+    if plan["kernel"] == 4:
+        if plan["tile_m"] == 16 and M <= 16:
+            return "tile_dyn_kernel"
+        if group == 128:
+            return "tile_deq_kernel" if os.environ.get("W4A16_TILE_DEQ") == "1" else "tile_group_kernel"
+    return KERNEL_NAMES.get(plan["kernel"], "?")
+
+
 def measured_traffic(key):
     try:
         with open(TRAFFIC_FILE) as f:
@@ -404,9 +416,7 @@ def main():
     line["roofline"].update({"traffic": measured_traffic("%s_M%d" % (args.config, args.M)),
                      "launches_per_step": 1 if res["plan"]["split"] == 1 or res["plan"]["workspace_bytes"] ==
                      8 * args.M * cfg.N else 2,
-                     "kernel": ("tile_group_kernel" if res["plan"]["kernel"] == 4 and cfg.group == 128 else
-                                "stripe_dyn_kernel" if res["plan"]["kernel"] == 3 and args.M <= 4 else
-                                KERNEL_NAMES.get(res["plan"]["kernel"], "?")),
+                     "kernel": kernel_name(res["plan"], args.M, cfg.group),
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"],
                      "algorithmic_flops_per_launch": 2.0 * args.M * cfg.K * cfg.N})
     line["cpu_baseline"] = cpu

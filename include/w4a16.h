@@ -227,9 +227,10 @@ int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, 
  *   "tile_dyn"       16 rows of X per workgroup: 1 = units of K always handed out by ticket, 2 = never
  *   "tile_depth"     units in flight per wave of that form (1, 2)
  *   "tile_waves"     waves per TILE workgroup (4..8)
- *   "tile_deq"       TILE beyond the ticket form, FP16, group 128: the weights dequantized to FP16 in registers
- *                    (Algorithm 1's Phase 1 as stated) instead of exact codes as MFMA operands: 1 = always, 2 = never
- *                    (the scheduler: at 64 rows of X per workgroup)
+ *   "tile_deq"       1: TILE beyond the ticket form, FP16, group 128: the weights dequantized to FP16 in registers
+ *                    (Algorithm 1's Phase 1 as stated: one rounding per weight, relative 2^-11) instead of exact codes as
+ *                    MFMA operands.  15 % faster at 64 rows of X per workgroup (M = 128, K = N = 8192), but the rounding
+ *                    spends up to half of the 1e-2 (1 + |ref|) tolerance there and more for longer K or larger X
  *   "log"            1: every w4a16_gemm* call prints its plan on stderr (the one case in which the library prints)
  * Returns W4A16_ERR_UNSUPPORTED for an unknown knob.
  */

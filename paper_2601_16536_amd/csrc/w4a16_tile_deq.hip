@@ -1,32 +1,28 @@
-// W4A16 multiply for many rows of X (M > 16), group = 128, FP16: the TILE family's
-// workgroup (one 64-column tile x 16 RT rows of X x one K slice, eight waves that
-// own contiguous runs of the slice's groups and meet in LDS), with Algorithm 1's
-// Phase 1 taken literally: a wave dequantizes its weights to FP16 in registers,
+// W4A16 multiply for many rows of X (M > 16), group = 128, FP16, an opt-in form (knob "tile_deq"): the TILE family's
+// workgroup (one 64-column tile x 16 RT rows of X x one K slice, eight waves that own contiguous runs of the
+// slice's groups and meet in LDS), with Algorithm 1's Phase 1 taken literally: a wave dequantizes its weights to
+// FP16 in registers,
 //     B = fp16(s (q - z))                                      (Eq. 2)
 // and the FP16 MFMA (Phase 2) accumulates x B over the wave's whole run in FP32.
 //
-// Why a second form beside w4a16_tile.hip (codes as exact subnormal operands,
-// scale and zero point applied per group in FP32): with 64 rows of X per
-// workgroup that form spends more vector-ALU than MFMA time (measured on
-// M = 128, K = N = 8192: vector ALU busy 42 %, MFMA 29 %, the two hardly
-// overlapping at two waves per SIMD): 2 FMAs per output element and group for
-// Eq. 2, a fifth MFMA per four for sum_k x_k, the 2^-4 scaling of every second x,
-// and two accumulator sets (128 registers) that leave no room to prepare the next
-// operands while the MFMAs of the current ones run.  Here the unpack costs more
-// (17 instead of 5 instructions per eight weights) but nothing else is left: no
-// step per group, no sum of x, X staged as it is, one accumulator set; the
-// registers that frees hold the next block's operands, unpacked while the
-// current block's MFMAs run, and two groups of weights in flight at every RT.
+// Why it exists beside w4a16_tile.hip (codes as exact subnormal operands, scale and zero point applied per group
+// in FP32): with 64 rows of X per workgroup that form is bound by instruction issue (measured on M = 128,
+// K = N = 8192: 115 vector instructions and 20 MFMAs per block of 32 k and wave, mostly one kind after the other):
+// 2 FMAs per output element and group for Eq. 2, a fifth MFMA per four for sum_k x_k, the 2^-4 scaling of every
+// second x, and two accumulator sets (128 registers) that leave no room to prepare the next operands while the MFMAs
+// of the current ones run.  Here the unpack costs more (16 instead of 5 instructions per eight weights) but nothing
+// else is left: no step per group, no sum of x, X staged as it is, one accumulator set; the registers that frees
+// hold the next block's operands, unpacked between the current block's MFMAs, and two groups of weights in flight:
+// 65 vector instructions and 16 MFMAs per block, 28.7 us against 33.3 us on that shape.
 //
-// The price is one FP16 rounding per weight (relative 2^-11), the paper's own
-// Phase 1; the M <= 16 forms keep exact weights.
+// Why it is not the scheduler's choice: the price is one FP16 rounding per weight (relative 2^-11), the paper's own
+// Phase 1.  Random in sign, it adds up to about sqrt(K) rms(x) rms(w) 2^-12.5: measured on that shape, every
+// output, 0.55 of the tolerance 1e-2 (1 + |ref|) where the exact-code form spends 0.05, and it grows with sqrt(K)
+// and with the magnitude of X (activations with outlier channels would exceed the tolerance).  At 32 and 16 rows
+// of X per workgroup, where fewer MFMAs share an unpacked word, it is also 5 to 15 % slower than the exact form.
 //
-// Unpack, eight codes of consecutive k in one 32-bit word w, operand k order
-// 0,1 | 2,3 | 4,5 | 6,7 (X needs no reordering):
-//     u = perm(bytes of w and w >> 4)   one code in bits 0-3 of each half
-//     t = (u & 0x000F000F) | 0x64006400 the FP16 pair 1024 + q       (exact)
-//     d = t - (1024 + z)                q - z                        (exact)
-//     B = d * s                         one rounding
+// Unpack, eight codes of consecutive k in one 32-bit word, operand k order 0,1 | 2,3 | 4,5 | 6,7 (X needs no
+// reordering): see dequant8.
 #include "w4a16_device.h"
 #include "w4a16_finish.h"
 #include "w4a16_internal.h"
