@@ -278,8 +278,10 @@ struct GroupShape {
     static constexpr int kChunkBlocks = RT == 4 ? 1 : 4;         // blocks per staged chunk of X
     static constexpr int kChunks = 4 / kChunkBlocks;             // chunks per group
     static constexpr int kRingGroups = RT == 4 ? 1 : 2;          // groups of weights in flight per wave (registers)
-    // LDS entries per packed row, padded: odd where sixteen lanes write sixteen packed rows of one row of X
-    static constexpr int kRowStride = kChunkBlocks == 4 ? kRowsX + 1 : kRowsX + 4;
+    // LDS entries per packed row, padded (a 16-byte LDS write goes eight lanes at a time over 32 banks): odd where
+    // neighbouring lanes write the packed rows of one row of X; rows + 2 where eight lanes are two rows of X x four packed
+    // rows (measured at 64 rows: SQ_LDS_BANK_CONFLICT three times lower than with rows + 4)
+    static constexpr int kRowStride = kChunkBlocks == 4 ? kRowsX + 1 : kRowsX + 2;
     static constexpr int kPerLane = kChunkBlocks * kBlockRows * kRowsX / 64;
     static constexpr int kBufBytes = kChunkBlocks * kBlockRows * kRowStride * 16;
     static constexpr int kWaveBytes = 2 * kBufBytes;
