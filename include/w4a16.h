@@ -84,8 +84,9 @@ typedef enum {
                                     share the slice (exact sums in LDS); slices of different workgroups meet in a
                                     64-bit fixed-point accumulator by one atomic add each, no second launch        */
     W4A16_KERNEL_TILE = 4        /* any M, the scheduler's choice otherwise: 64-column tile x 16, 32 or 64 rows of X
-                                    per workgroup, its waves own contiguous runs of K (LDS reduction), plain MFMA
-                                    operand layout; slices of different workgroups meet as in STRIPE                */
+                                    per workgroup, its waves (eight; four at 64 rows) own contiguous runs of K (LDS
+                                    reduction), plain MFMA operand layout; slices of different workgroups meet as
+                                    in STRIPE                                                                         */
 } w4a16_kernel;
 
 /* What the scheduler decided for a shape (Algorithm 1 takes S and the block
@@ -227,6 +228,8 @@ int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, 
  *   "tile_dyn"       16 rows of X per workgroup: 1 = units of K always handed out by ticket, 2 = never
  *   "tile_depth"     units in flight per wave of that form (1, 2)
  *   "tile_waves"     waves per TILE workgroup (4..8)
+ *   "tile_wide"      2: TILE at 64 rows of X per workgroup, FP16, group 128: the eight-wave form instead of the
+ *                    four-wave one
  *   "tile_deq"       1: TILE beyond the ticket form, FP16, group 128: the weights dequantized to FP16 in registers
  *                    (Algorithm 1's Phase 1 as stated: one rounding per weight, relative 2^-11) instead of exact codes as
  *                    MFMA operands.  15 % faster at 64 rows of X per workgroup (M = 128, K = N = 8192), but the rounding

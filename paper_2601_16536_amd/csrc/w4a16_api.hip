@@ -65,6 +65,7 @@ struct Tuning {
     int tile_waves = 0;     // waves per TILE workgroup (4..8)
     int tile_deq = 0;       // 1: TILE beyond the ticket form, FP16, group 128: the weights dequantized to FP16 in registers (one
                             // rounding per weight, the paper's Phase 1) instead of exact codes as operands
+    int tile_wide = 0;      // TILE at 64 rows of X per workgroup, FP16, group 128: 2 = the eight-wave form instead of the four-wave one
     int log = 0;            // 1: every call prints its plan on stderr
 };
 
@@ -76,7 +77,8 @@ const Knob kKnobs[] = {
     {"stripe_finish", &Tuning::stripe_finish}, {"stripe_waves", &Tuning::stripe_waves}, {"stripe_dyn", &Tuning::stripe_dyn},
     {"stripe_unit", &Tuning::stripe_unit},     {"stripe_depth", &Tuning::stripe_depth}, {"stripe_dot2", &Tuning::stripe_dot2},
     {"tile_rows", &Tuning::tile_rows},         {"tile_dyn", &Tuning::tile_dyn},         {"tile_depth", &Tuning::tile_depth},
-    {"tile_waves", &Tuning::tile_waves},       {"tile_deq", &Tuning::tile_deq},         {"log", &Tuning::log},
+    {"tile_waves", &Tuning::tile_waves},       {"tile_deq", &Tuning::tile_deq},         {"tile_wide", &Tuning::tile_wide},
+    {"log", &Tuning::log},
 };
 
 Tuning &tuning()
@@ -191,6 +193,10 @@ bool stripe_by_ticket(int M) { return M <= 4 && tuning().stripe_dyn != 2; }
 // with several row blocks, which re-read the weights from the L2, 3 % slower).
 bool tile_by_ticket(int M, int rows_x) { return rows_x == 16 && (tuning().tile_dyn == 1 || (M <= 16 && tuning().tile_dyn != 2)); }
 
+// TILE at 64 rows of X per workgroup and group = 128: four waves per workgroup, each alone on its SIMD
+// (w4a16_tile_wide.hip; FP16 only: BF16 activations run such a plan with the eight-wave form).
+bool tile_wide(int rows_x, int group) { return rows_x == 64 && group == 128 && tuning().tile_wide != 2; }
+
 // LDS a STRIPE workgroup needs for a slice of gps groups, and the most it may use.
 size_t stripe_lds(int M, int group, int gps, int waves)
 {
@@ -267,6 +273,7 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         p->tile_m = rows_x;
         const int tw = tuning().tile_waves;
         if (tw >= 4 && tw <= (tile_by_ticket(M, rows_x) ? 16 : 8)) { p->waves_k = tw; p->threads = 64 * tw; }
+        if (tile_wide(rows_x, group)) { p->waves_k = 4; p->threads = 256; }
         const long long wgs = tiles * ((M + rows_x - 1) / rows_x);
         if (S == 0) S = (int)(cus / wgs);  // never more workgroups than compute units: the extra ones would run as a second round
         if (S < 1) S = 1;
@@ -487,9 +494,12 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
         // Opt-in only.  Measured on M = 128, K = N = 8192 (64 rows of X per workgroup): 28.7 us against 33.3 us with exact
         // codes as operands, but the FP16 rounding of every weight spends up to 0.55 of the tolerance there (0.05
         // with exact codes), grows with sqrt(K) and with the magnitude of X; at 32 and 16 rows it is also 5 to 15 % slower.
-        e = launch_tile_deq(a, finish, b.sync, plan.tile_m, plan.waves_k, st);
+        e = launch_tile_deq(a, finish, b.sync, plan.tile_m, tile_wide(plan.tile_m, group) ? 8 : plan.waves_k, st);
+    } else if (plan.kernel == W4A16_KERNEL_TILE && tile_wide(plan.tile_m, group) && !bf16) {
+        // four waves with the whole register file each; measured on M = 128, K = N = 8192: 30.9 us against 33.1 us with eight
+        e = launch_tile_wide(a, finish, b.sync, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE) {
-        e = launch_tile(a, finish, b.sync, plan.tile_m, plan.waves_k, st);
+        e = launch_tile(a, finish, b.sync, plan.tile_m, tile_wide(plan.tile_m, group) ? 8 : plan.waves_k, st);
     } else {
         e = launch_wave_split(a, plan.tile_n, st);
     }

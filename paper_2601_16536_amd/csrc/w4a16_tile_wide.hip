@@ -1,0 +1,346 @@
+// W4A16 multiply, TILE family at 64 rows of X per workgroup (M > 32 on wide matrices), FP16, group = 128: one workgroup
+// of FOUR waves per (64-column tile, 64 rows of X, K slice), each wave alone on its SIMD with the whole register file.
+//
+// Why this form.  At 64 rows a wave issues 16 MFMAs 16x16x32 per block of 32 k, and what bounds the kernel is
+// instruction issue (measured on M = 128, K = N = 8192): a vector instruction costs a wave 4 cycles, an MFMA 8 when
+// vector instructions sit between it and the previous MFMA, 16 when it follows another MFMA.  The eight-wave form
+// (w4a16_tile.hip) has 238 registers per wave: one group of weights in flight, X one block ahead, operands prepared
+// just before their MFMAs, 95 vector instructions and 20 MFMAs per block, one kind after the other, and the waves
+// wait a quarter of their time.  With four waves a wave has 512 registers, enough to
+//   - keep the arithmetic exact and still drop the sum of x: the B operand is q - z as an exact FP16 integer
+//     (two vector instructions more per word than the bare code, but no fifth MFMA per four, no 2^-4 scaling of X,
+//     and Eq. 2's step is one FMA per output element and group, s (sum_k x_k (q_k - z)), instead of two);
+//   - hold two sets of per-group sums, so that the step of one group is spread between the MFMAs of the next;
+//   - unpack the next block's operands and fetch its X operands from LDS between the MFMAs of the current block;
+//   - keep four groups of weights and two chunks of X in flight (loads return to a wave in the order it asked, so X
+//     must be asked for as far ahead as the weights that were asked for just before it).
+// Arithmetic: products x (q - z) are exact in FP32, sums over a group in FP32 inside the MFMA, times s in FP32: the
+// same values as the eight-wave form up to the order of the FP32 sums.
+#include "w4a16_device.h"
+#include "w4a16_finish.h"
+#include "w4a16_internal.h"
+#include <type_traits>
+
+namespace w4a16 {
+namespace {
+
+constexpr int kTileCols = 64;
+constexpr int kRowsX = 64;
+constexpr int kRT = 4;          // row tiles of 16
+constexpr int kBlockRows = 4;   // packed rows per block: one MFMA step of 32 k
+constexpr int kBpg = 4;         // blocks per group (group = 128)
+constexpr int kXcds = 8;
+constexpr int kWaves = 4;
+constexpr int kRing = 4;        // groups of weights in flight per wave (registers)
+constexpr int kChunkBlocks = 2; // blocks per staged chunk of X: whole 128-byte lines of a row
+constexpr int kLanesPerRow = 4 * kChunkBlocks;   // lanes that fetch one row's 128 bytes of a chunk (16 bytes each)
+constexpr int kRowsPerLoad = 64 / kLanesPerRow;  // rows of X one wave-wide load covers
+constexpr int kPerLane = kRowsX / kRowsPerLoad;  // loads per lane and chunk
+constexpr int kRowStride = kRowsX + 1;           // LDS entries per packed row: odd, so that the eight lanes of a write pass
+                                                 // (one row of X, eight packed rows) hit different banks
+constexpr int kBufBytes = kChunkBlocks * kBlockRows * kRowStride * 16;
+constexpr int kWaveBytes = 2 * kBufBytes;
+
+// -(1024 + z) and -(64 + z) for the four columns of a lane, and their scales as floats
+struct GroupConst {
+    uint32_t negz[4];
+    float s[4];
+};
+__device__ __forceinline__ GroupConst group_const(uint2_t sc, uint32_t z)
+{
+    GroupConst g;
+    H2 s01, s23;
+    s01.u = sc[0];
+    s23.u = sc[1];
+    g.s[0] = (float)s01.h[0];
+    g.s[1] = (float)s01.h[1];
+    g.s[2] = (float)s23.h[0];
+    g.s[3] = (float)s23.h[1];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) g.negz[c] = (((z >> (4 * c)) & 15u) * 0x00100001u) | 0xD400E400u;  // sign | 64 or 1024 | z in the bits that count ones
+    return g;
+}
+
+// One column's word -> q - z for its eight k, k ascending, as exact FP16 integers.  Byte e of the word holds the codes
+// of k = 2e (bits 0-3) and 2e + 1 (bits 4-7); left where they are, under the exponent of 1024 (unit in the last place
+// 1) and of 64 (unit 2^-4, i.e. bits 4-7 count ones), they read 1024 + q and 64 + q; minus 1024 + z and 64 + z.
+__device__ __forceinline__ half8_t codes_minus_zero(uint32_t w, uint32_t negz, uint32_t mask, uint32_t magic)
+{
+    H2 zv;
+    zv.u = negz;
+    H8 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        // byte selectors of v_perm_b32: 0-3 pick from the second operand, 0x0c gives zero: byte e into both halves
+        const uint32_t u = __builtin_amdgcn_perm(w, w, 0x0C000C00u + 0x00010001u * (uint32_t)e);
+        H2 t;
+        t.u = (u & mask) | magic;
+        t.h = t.h + zv.h;
+        r.u[e] = t.u;
+    }
+    return r.h;
+}
+
+__global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync, const int row_blocks, const int red_waves)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g4 = lane >> 4, j = lane & 15;
+
+    // workgroup -> (column tile, K slice, row block): the row blocks of one (tile, slice) are neighbours on one XCD
+    // (workgroup b runs on XCD b mod 8) and start together: the second reader finds the weights in that XCD's L2
+    const int ntiles = (a.N + kTileCols - 1) / kTileCols;
+    const int units = ntiles * a.split;
+    int rb = 0, unit = (int)blockIdx.x;
+    if (row_blocks > 1) {
+        const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+        rb = local % row_blocks;
+        unit = (local / row_blocks) * kXcds + xcd;
+    }
+    if (unit >= units) return;  // the grid is rounded up to whole XCD rounds
+    int tile = unit, slice = 0;
+    if (a.split > 1) {
+        slice = unit / ntiles;
+        tile = unit - slice * ntiles;
+    }
+    const int m0 = rb * kRowsX;
+    const int col0 = tile * kTileCols + 4 * j;
+    const bool ok = col0 < a.N;
+
+    // the slice's groups, and this wave's run of them: groups / waves each, the first groups % waves one more
+    const int gbeg = slice * a.groups_per_split;
+    int gend = gbeg + a.groups_per_split;
+    if (gend > a.groups) gend = a.groups;
+    const int groups = gend - gbeg;
+    const int per = (int)((uint32_t)groups / (uint32_t)kWaves), extra = groups - per * kWaves;
+    const int g0 = gbeg + per * wave + (wave < extra ? wave : extra);
+    const int ng = per + (wave < extra ? 1 : 0);
+
+    // every buffer descriptor ends where the wave's run ends: loads past the run are cut off by the hardware's
+    // range check (zeros, no traffic)
+    const uint32_t row_w = (uint32_t)a.N * 4u, row_s = (uint32_t)a.N * 2u, row_z = (uint32_t)(a.N >> 3) * 4u;
+    const uint32_t step_w = kBlockRows * row_w;  // one block further
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t *>(a.Wp) + (size_t)g0 * 16 * a.N, 0, (uint32_t)ng * 16u * row_w, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(a.scales) + (size_t)g0 * a.N, 0, (uint32_t)ng * row_s, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t *>(a.Zp) + (size_t)g0 * (a.N >> 3), 0, zero_point_bytes(a.Zp, (uint32_t)ng * row_z), kRawBuffer);
+    const uint32_t zfill = symmetric_fill(a.Zp);
+    const uint32_t zsh = (uint32_t)(col0 & 4) * 4u;  // this lane's four nibbles in its zero-point word
+    uint32_t vw = ok ? (uint32_t)(g4 * a.N + col0) * 4u : kOutOfRange;  // running offsets of the next block / group to load
+    uint32_t vs = ok ? (uint32_t)col0 * 2u : kOutOfRange;
+    uint32_t vz = ok ? (uint32_t)(col0 >> 3) * 4u : kOutOfRange;
+
+    uint4_t wq[kRing * kBpg];  // the weights in flight
+    auto load_w = [&](uint4_t &d) {
+        d = __builtin_amdgcn_raw_buffer_load_b128(rw, vw, 0, 2);  // read once from DRAM: nontemporal
+        vw += step_w;
+    };
+    // The scales and zero points of the groups in flight, asked for just ahead of their group's weights.
+    uint2_t scq[kRing];
+    uint32_t zwq[kRing];
+    auto load_sz = [&](int place) {
+        scq[place] = __builtin_amdgcn_raw_buffer_load_b64(rs, vs, 0, 0);
+        zwq[place] = __builtin_amdgcn_raw_buffer_load_b32(rz, vz, 0, 0);
+        vs += row_s;
+        vz += row_z;
+    };
+
+    // ---- X: this wave's LDS (two chunk buffers), two register sets of chunks in flight ----
+    // kLanesPerRow neighbouring lanes fetch the 128 contiguous bytes a chunk takes of one row of X; load q of a lane:
+    // row q kRowsPerLoad + lane / kLanesPerRow, packed row lane % kLanesPerRow of the chunk.  X is staged as it is:
+    // the operand order of codes_minus_zero is the order of k.
+    unsigned char *wl = smem + (size_t)wave * kWaveBytes;
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(a.X), 0, (uint32_t)((size_t)a.M * a.K * 2), kRawBuffer);
+    uint32_t xg[kPerLane];
+#pragma unroll
+    for (int q = 0; q < kPerLane; ++q) {
+        const uint32_t m = (uint32_t)m0 + (uint32_t)(q * kRowsPerLoad + lane / kLanesPerRow);
+        const uint32_t prow = (uint32_t)g0 * 16u + (uint32_t)(lane % kLanesPerRow);
+        xg[q] = m < (uint32_t)a.M ? (m * (uint32_t)a.K + prow * 8u) * 2u : kOutOfRange;
+    }
+    const uint32_t xl0 = (uint32_t)(((lane % kLanesPerRow) * kRowStride + lane / kLanesPerRow) * 16);
+    uint4_t xd[2][kPerLane];
+    const uint32_t nchunks = (uint32_t)ng * 2u;
+    auto x_load = [&](uint4_t(&d)[kPerLane], uint32_t chunk) {  // chunk of the wave's run (past it: out of range, zeros)
+        const uint32_t so = chunk * (kChunkBlocks * kBlockRows * 16u);
+#pragma unroll
+        for (int q = 0; q < kPerLane; ++q) d[q] = __builtin_amdgcn_raw_buffer_load_b128(rx, chunk < nchunks ? xg[q] : kOutOfRange, so, 0);
+    };
+    auto x_store = [&](const uint4_t(&d)[kPerLane], int par) {
+#pragma unroll
+        for (int q = 0; q < kPerLane; ++q)
+            *reinterpret_cast<uint4_t *>(wl + par * kBufBytes + xl0 + q * kRowsPerLoad * 16) = d[q];
+    };
+
+    float4_t tot[kRT][4];
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) tot[rt][c] = (float4_t){0.f, 0.f, 0.f, 0.f};
+
+    if (ng > 0) {
+        // X of the first two chunks and each group's scales go ahead of that group's weights: loads return in order
+        x_load(xd[0], 0);
+        x_load(xd[1], 1);
+#pragma unroll
+        for (int h = 0; h < kRing; ++h) {
+            load_sz(h);
+#pragma unroll
+            for (int p = 0; p < kBpg; ++p) load_w(wq[h * kBpg + p]);
+        }
+        x_store(xd[0], 0);
+        x_load(xd[0], 2);
+
+        const uint32_t xa0 = (uint32_t)(wave * kWaveBytes + (g4 * kRowStride + j) * 16);  // A entry of block 0, row tile 0, buffer 0
+        uint32_t mask = 0x00F0000Fu, magic = 0x54006400u;
+        asm volatile("" : "+v"(mask), "+v"(magic));  // kept in vector registers: v_and_or_b32 has no room for two constants
+        const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
+
+        // operands of the block in use and of the next one; per-group sums of the group in use and of the one before
+        half8_t bop[2][4];
+        H8 xop[2][kRT];
+        float4_t part[2][kRT][4];
+        GroupConst gc = group_const(scq[0], (zwq[0] | zfill) >> zsh);
+        float s_prev[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) bop[0][c] = codes_minus_zero(wq[0][c], gc.negz[c], mask, magic);
+        load_sz(0);     // the same place, and its first block, kRing groups on (past the run: zeros, no traffic)
+        load_w(wq[0]);
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) part[1][rt][c] = zero4;  // "the group before the first": nothing
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) xop[0][rt].u = *reinterpret_cast<const uint4_t *>(smem + xa0 + rt * 256);
+
+        // One group from ring place R.  Its chunk c sits in LDS buffer c.  Entering, bop[0] and xop[0] hold its first
+        // block, gc its constants, s_prev and part[(R + 1) & 1] the previous group's scales and sums.  Only this
+        // wave touches its LDS and the LDS operations of one wave complete in order; the fences only keep the
+        // compiler from moving them across the staging.
+        auto do_group = [&](auto place, const uint32_t gi) {
+            constexpr int R = decltype(place)::value;
+            constexpr int RN = (R + 1) % kRing;
+            constexpr int PC = R & 1, PP = PC ^ 1;  // sums of this group, of the previous one
+            float s_next[4];
+#pragma unroll
+            for (int p = 0; p < kBpg; ++p) {
+                const int c = p / kChunkBlocks, lb = p % kChunkBlocks;
+                // the next block's operands, independent of the MFMAs below
+                if (p + 1 < kBpg) {
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) bop[(p + 1) & 1][cc] = codes_minus_zero(wq[R * kBpg + p + 1][cc], gc.negz[cc], mask, magic);
+                    load_w(wq[R * kBpg + p + 1]);  // the same block kRing groups on
+                } else {
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) s_next[cc] = gc.s[cc];
+                    gc = group_const(scq[RN], (zwq[RN] | zfill) >> zsh);  // the next group's first block
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) bop[0][cc] = codes_minus_zero(wq[RN * kBpg][cc], gc.negz[cc], mask, magic);
+                    load_sz(RN);
+                    load_w(wq[RN * kBpg]);
+                }
+                if (lb == kChunkBlocks - 1) {
+                    // The chunk's last block is in registers (xop[p & 1]).  The chunk after it, asked for two chunks
+                    // ago, goes to the other buffer (last read a chunk ago), and the chunk after the next is asked for.
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    x_store(xd[c ^ 1], c ^ 1);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    x_load(xd[c ^ 1], gi * 2 + c + 3);
+                }
+                // the next block's X operands: the other block of this chunk, or the first of the next chunk
+                {
+                    const int pn = (p + 1) % kBpg, cn = pn / kChunkBlocks, lbn = pn % kChunkBlocks;
+                    const unsigned char *xb = smem + xa0 + cn * kBufBytes + lbn * (kBlockRows * kRowStride * 16);
+#pragma unroll
+                    for (int rt = 0; rt < kRT; ++rt) xop[(p + 1) & 1][rt].u = *reinterpret_cast<const uint4_t *>(xb + rt * 256);
+                }
+                // this block's MFMAs
+#pragma unroll
+                for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc)
+                        part[PC][rt][cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xop[p & 1][rt].h, bop[p & 1][cc], p == 0 ? zero4 : part[PC][rt][cc], 0, 0, 0);
+                // Eq. 2's step for a quarter of the previous group: its row tile p
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) tot[p][cc][i] = __builtin_fmaf(s_prev[cc], part[PP][p][cc][i], tot[p][cc][i]);
+                // the schedule of the block: every MFMA followed by its share of the vector instructions around it
+#pragma unroll
+                for (int i = 0; i < 4 * kRT; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                }
+            }
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) s_prev[cc] = s_next[cc];
+        };
+
+        for (uint32_t gi = 0; gi < (uint32_t)ng; gi += kRing) {
+            do_group(std::integral_constant<int, 0>{}, gi);
+            if (gi + 1 < (uint32_t)ng) do_group(std::integral_constant<int, 1>{}, gi + 1);
+            if (gi + 2 < (uint32_t)ng) do_group(std::integral_constant<int, 2>{}, gi + 2);
+            if (gi + 3 < (uint32_t)ng) do_group(std::integral_constant<int, 3>{}, gi + 3);
+        }
+        // the last group's step
+        const int last = (ng - 1) & 1;
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    tot[rt][cc][i] = __builtin_fmaf(s_prev[cc], (last ? part[1][rt][cc][i] : part[0][rt][cc][i]), tot[rt][cc][i]);
+    }
+
+    // Phase 3 inside the workgroup, then across workgroups (see w4a16_finish.h).  The sums are regrouped
+    // here, once, into the four neighbouring columns a lane hands over per row.
+    float4_t mine4[kRT][4];
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mine4[rt][i] = (float4_t){tot[rt][0][i], tot[rt][1][i], tot[rt][2][i], tot[rt][3][i]};
+    const auto write_mine = [&](float4_t *mine) {  // [row][column / 4] of the 64-column tile
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = mine4[rt][i];
+    };
+    if (finish == kFinishAccumulator)
+        reduce_and_finish<ActF16, kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+    else
+        reduce_and_finish<ActF16, kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+}
+
+}  // namespace
+
+hipError_t launch_tile_wide(const GemmArgs &a, int finish, unsigned long long *sync, hipStream_t stream)
+{
+    if (a.group != 128 || a.bf16) return hipErrorInvalidValue;
+    if (!finish_args_ok(a, finish, sync)) return hipErrorInvalidValue;
+    const unsigned long long rows = (unsigned long long)a.groups_per_split * (a.group / 8);
+    if (rows * a.N * 4ull >= 0x7F000000ull) return hipErrorInvalidValue;  // slice-relative 32-bit buffer offsets
+    if ((unsigned long long)a.M * a.K * 2ull >= 0x7F000000ull) return hipErrorInvalidValue;
+    const size_t stage = (size_t)kWaves * kWaveBytes;
+    const size_t one = (size_t)kRowsX * kTileCols * 4;  // a wave's result tile in fp32: the final sums reuse the space
+    const size_t red = one * kWaves;
+    const size_t lds = stage > red ? stage : red;
+    const int red_waves = kWaves;
+    const int ntiles = (a.N + kTileCols - 1) / kTileCols;
+    const int row_blocks = (a.M + kRowsX - 1) / kRowsX;
+    const long long grid = ((long long)ntiles * a.split + kXcds - 1) / kXcds * kXcds * row_blocks;
+    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(tile_wide_kernel, dim3((unsigned)grid), dim3(64 * kWaves), lds, stream, a, finish, sync, row_blocks, red_waves);
+    return hipGetLastError();
+}
+
+}  // namespace w4a16

@@ -89,23 +89,28 @@ def test_small_shapes_every_split(gpu, M, K, N, group):
             assert r <= 1.0, (M, K, N, group, kernel, split, r)
 
 
-@pytest.mark.parametrize("deq", [0, 1])
+@pytest.mark.parametrize("deq", [0, 1, 2])
 @pytest.mark.parametrize("rows_x", [16, 32, 64])
 def test_tile_family_every_row_block(gpu, rows_x, deq):
-    """The TILE kernels for 16, 32 and 64 rows of X per workgroup, in both forms (exact codes as MFMA operands;
-    opt-in, group = 128 only: weights dequantized to FP16 in registers).  The scheduler takes the larger blocks
+    """The TILE kernels for 16, 32 and 64 rows of X per workgroup: the scheduler's forms (at 64 rows and group = 128 four
+    waves per workgroup with q - z as the operand), the opt-in form with weights dequantized to FP16 in registers
+    (deq = 1), and the eight-wave form at 64 rows (deq = 2).  The scheduler takes the larger blocks
     only where N is large, so the library's tuning knobs force them here on small ragged shapes
     (rows past M, columns past N, fewer groups than waves, group sizes with and without the
     group-aligned loop)."""
     _, binding = gpu
+    if deq == 2 and rows_x != 64:
+        pytest.skip("the four-wave form exists at 64 rows only")
     binding.tune("tile_rows", rows_x)
-    binding.tune("tile_deq", deq)
+    binding.tune("tile_deq", 1 if deq == 1 else 0)
+    binding.tune("tile_wide", 2 if deq == 2 else 0)  # deq == 2: the eight-wave form at 64 rows instead of the four-wave one
     binding.tune("tile_dyn", 2)  # not the ticket form, which 16 rows would take
     try:
         _tile_rows_cases(gpu, rows_x)
     finally:
         binding.tune("tile_rows", 0)
         binding.tune("tile_deq", 0)
+        binding.tune("tile_wide", 0)
         binding.tune("tile_dyn", 0)
 
 
