@@ -230,10 +230,6 @@ int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, 
  *   "tile_waves"     waves per TILE workgroup (4..8)
  *   "tile_wide"      2: TILE at 64 rows of X per workgroup, FP16, group 128: the eight-wave form instead of the
  *                    four-wave one
- *   "tile_deq"       1: TILE beyond the ticket form, FP16, group 128: the weights dequantized to FP16 in registers
- *                    (Algorithm 1's Phase 1 as stated: one rounding per weight, relative 2^-11) instead of exact codes as
- *                    MFMA operands.  15 % faster at 64 rows of X per workgroup (M = 128, K = N = 8192), but the rounding
- *                    spends up to half of the 1e-2 (1 + |ref|) tolerance there and more for longer K or larger X
  *   "log"            1: every w4a16_gemm* call prints its plan on stderr (the one case in which the library prints)
  * Returns W4A16_ERR_UNSUPPORTED for an unknown knob.
  */

@@ -26,13 +26,19 @@ FLAGS = [
 ]
 
 
+# Per-file additions.  The four-wave tile kernel reads its MFMA results back with vector instructions (Eq. 2's step per
+# group): with the results in accumulation registers, the compiler's default under register pressure, every read costs
+# a v_accvgpr_read first.
+FILE_FLAGS = {"w4a16_tile_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
 def _compile(src: str, extra=(), objdir: str = OBJ) -> str:
     obj = os.path.join(objdir, os.path.basename(src)[:-4] + ".o")
-    cmd = [HIPCC, *FLAGS, *extra, "-c", src, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(os.path.basename(src), []), *extra, "-c", src, "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode:

@@ -63,8 +63,6 @@ struct Tuning {
     int tile_dyn = 0;       // 16 rows of X per workgroup: 1 = units always handed out by ticket, 2 = never (equal runs per wave)
     int tile_depth = 0;     // units in flight per wave of the ticket form (1, 2)
     int tile_waves = 0;     // waves per TILE workgroup (4..8)
-    int tile_deq = 0;       // 1: TILE beyond the ticket form, FP16, group 128: the weights dequantized to FP16 in registers (one
-                            // rounding per weight, the paper's Phase 1) instead of exact codes as operands
     int tile_wide = 0;      // TILE at 64 rows of X per workgroup, FP16, group 128: 2 = the eight-wave form instead of the four-wave one
     int log = 0;            // 1: every call prints its plan on stderr
 };
@@ -77,7 +75,7 @@ const Knob kKnobs[] = {
     {"stripe_finish", &Tuning::stripe_finish}, {"stripe_waves", &Tuning::stripe_waves}, {"stripe_dyn", &Tuning::stripe_dyn},
     {"stripe_unit", &Tuning::stripe_unit},     {"stripe_depth", &Tuning::stripe_depth}, {"stripe_dot2", &Tuning::stripe_dot2},
     {"tile_rows", &Tuning::tile_rows},         {"tile_dyn", &Tuning::tile_dyn},         {"tile_depth", &Tuning::tile_depth},
-    {"tile_waves", &Tuning::tile_waves},       {"tile_deq", &Tuning::tile_deq},         {"tile_wide", &Tuning::tile_wide},
+    {"tile_waves", &Tuning::tile_waves},       {"tile_wide", &Tuning::tile_wide},
     {"log", &Tuning::log},
 };
 
@@ -490,13 +488,8 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
         e = launch_stripe(a, finish, b.sync, plan.waves_k, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE && tile_by_ticket(M, plan.tile_m)) {
         e = launch_tile_dyn(a, finish, b.sync, plan.waves_k, tuning().tile_depth == 2 && !bf16 ? 2 : 1, st);
-    } else if (plan.kernel == W4A16_KERNEL_TILE && group == 128 && !bf16 && tuning().tile_deq == 1) {
-        // Opt-in only.  Measured on M = 128, K = N = 8192 (64 rows of X per workgroup): 28.7 us against 33.3 us with exact
-        // codes as operands, but the FP16 rounding of every weight spends up to 0.55 of the tolerance there (0.05
-        // with exact codes), grows with sqrt(K) and with the magnitude of X; at 32 and 16 rows it is also 5 to 15 % slower.
-        e = launch_tile_deq(a, finish, b.sync, plan.tile_m, tile_wide(plan.tile_m, group) ? 8 : plan.waves_k, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE && tile_wide(plan.tile_m, group) && !bf16) {
-        // four waves with the whole register file each; measured on M = 128, K = N = 8192: 30.9 us against 33.1 us with eight
+        // four waves with the whole register file each; measured on M = 128, K = N = 8192: 27.5 us against 33.1 us with eight
         e = launch_tile_wide(a, finish, b.sync, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE) {
         e = launch_tile(a, finish, b.sync, plan.tile_m, tile_wide(plan.tile_m, group) ? 8 : plan.waves_k, st);

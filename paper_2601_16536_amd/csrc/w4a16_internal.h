@@ -62,8 +62,6 @@ int stripe_dyn_lds_limit();                                           // most it
 // workgroup, `waves` (4..8) waves per workgroup that split the K slice; `finish` and `sync` as in the STRIPE
 // family.
 hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, int waves, hipStream_t stream);
-// TILE family, FP16, group = 128: the weights dequantized to FP16 in registers (w4a16_tile_deq.hip); arguments as launch_tile.
-hipError_t launch_tile_deq(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, int waves, hipStream_t stream);
 // TILE family at 64 rows of X per workgroup, FP16, group = 128: four waves per workgroup (w4a16_tile_wide.hip).
 hipError_t launch_tile_wide(const GemmArgs &a, int finish, unsigned long long *sync, hipStream_t stream);
 // TILE family, 16 rows of X per workgroup, the slice handed out to the waves by ticket (w4a16_tile_dyn.hip); `depth` (1, 2)

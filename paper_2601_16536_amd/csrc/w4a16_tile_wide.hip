@@ -10,10 +10,11 @@
 //   - keep the arithmetic exact and still drop the sum of x: the B operand is q - z as an exact FP16 integer
 //     (two vector instructions more per word than the bare code, but no fifth MFMA per four, no 2^-4 scaling of X,
 //     and Eq. 2's step is one FMA per output element and group, s (sum_k x_k (q_k - z)), instead of two);
-//   - hold two sets of per-group sums, so that the step of one group is spread between the MFMAs of the next;
+//   - put the step of one group between the first MFMAs of the next (tile by tile: step, then the MFMA that restarts
+//     the tile's sums);
 //   - unpack the next block's operands and fetch its X operands from LDS between the MFMAs of the current block;
-//   - keep four groups of weights and two chunks of X in flight (loads return to a wave in the order it asked, so X
-//     must be asked for as far ahead as the weights that were asked for just before it).
+//   - keep two groups of weights in flight, and X three chunks ahead, loaded straight into LDS (loads return to a
+//     wave in the order it asked, so X must be asked for as far ahead as the weights that were asked for just before).
 // Arithmetic: products x (q - z) are exact in FP32, sums over a group in FP32 inside the MFMA, times s in FP32: the
 // same values as the eight-wave form up to the order of the FP32 sums.
 #include "w4a16_device.h"
@@ -31,24 +32,29 @@ constexpr int kBlockRows = 4;   // packed rows per block: one MFMA step of 32 k
 constexpr int kBpg = 4;         // blocks per group (group = 128)
 constexpr int kXcds = 8;
 constexpr int kWaves = 4;
-constexpr int kRing = 4;        // groups of weights in flight per wave (registers)
+constexpr int kRing = 2;        // groups of weights in flight per wave (registers): eight blocks, about 3 us, ahead
 constexpr int kChunkBlocks = 2; // blocks per staged chunk of X: whole 128-byte lines of a row
-constexpr int kLanesPerRow = 4 * kChunkBlocks;   // lanes that fetch one row's 128 bytes of a chunk (16 bytes each)
-constexpr int kRowsPerLoad = 64 / kLanesPerRow;  // rows of X one wave-wide load covers
-constexpr int kPerLane = kRowsX / kRowsPerLoad;  // loads per lane and chunk
-constexpr int kRowStride = kRowsX + 1;           // LDS entries per packed row: odd, so that the eight lanes of a write pass
-                                                 // (one row of X, eight packed rows) hit different banks
-constexpr int kBufBytes = kChunkBlocks * kBlockRows * kRowStride * 16;
-constexpr int kWaveBytes = 2 * kBufBytes;
+constexpr int kLoadsPerChunk = 8;                // wave-wide loads per chunk: eight rows of X each, 1 KiB
+constexpr int kBufBytes = kLoadsPerChunk * 1024; // a chunk in LDS: 64 rows x 128 bytes, no padding
+constexpr int kBuffers = 4;                      // chunks of X per wave in LDS: the one in use and three on their way
+constexpr int kWaveBytes = kBuffers * kBufBytes;
+// Vector-memory operations a wave issues per group, in program order (see do_group):
+//   block 0: W; block 1: W, X x 8; block 2: W; block 3: scales, zero points, W, X x 8.
+// The compiler does not know that the loads into LDS must have landed before the LDS reads that use them: the waits
+// are written by hand, as the number of operations that may still be on their way (loads return in order).
+constexpr int kWaitChunk1 = 24;  // at block 1, for the group's second chunk, asked for at block 3 two groups ago: one whole
+                                 // group (22) + W + W since then
+constexpr int kWaitChunk0 = 26;  // at block 3, for the next group's first chunk, asked for at block 1 of the group before:
+                                 // W, scales, zero points, W, X x 8 (12) + W, W, X x 8, W, scales, zero points, W (14)
 
-// -(1024 + z) and -(64 + z) for the four columns of a lane, and their scales as floats
+// The B operand q - z, exact in either 16-bit format, and what it takes per group: for the four columns of a lane the
+// pair to subtract and the scale as a float.
 struct GroupConst {
     uint32_t negz[4];
     float s[4];
 };
-__device__ __forceinline__ GroupConst group_const(uint2_t sc, uint32_t z)
+__device__ __forceinline__ void group_scales(GroupConst &g, uint2_t sc)
 {
-    GroupConst g;
     H2 s01, s23;
     s01.u = sc[0];
     s23.u = sc[1];
@@ -56,31 +62,44 @@ __device__ __forceinline__ GroupConst group_const(uint2_t sc, uint32_t z)
     g.s[1] = (float)s01.h[1];
     g.s[2] = (float)s23.h[0];
     g.s[3] = (float)s23.h[1];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) g.negz[c] = (((z >> (4 * c)) & 15u) * 0x00100001u) | 0xD400E400u;  // sign | 64 or 1024 | z in the bits that count ones
-    return g;
 }
 
-// One column's word -> q - z for its eight k, k ascending, as exact FP16 integers.  Byte e of the word holds the codes
-// of k = 2e (bits 0-3) and 2e + 1 (bits 4-7); left where they are, under the exponent of 1024 (unit in the last place
-// 1) and of 64 (unit 2^-4, i.e. bits 4-7 count ones), they read 1024 + q and 64 + q; minus 1024 + z and 64 + z.
-__device__ __forceinline__ half8_t codes_minus_zero(uint32_t w, uint32_t negz, uint32_t mask, uint32_t magic)
-{
-    H2 zv;
-    zv.u = negz;
-    H8 r;
+// FP16.  Byte e of a column's word holds the codes of k = 2e (bits 0-3) and 2e + 1 (bits 4-7); copied into both
+// halves of a register and left where they are, under the exponent of 1024 (unit in the last place 1) and of 64 (unit
+// 2^-4, i.e. bits 4-7 count ones), they read 1024 + q and 64 + q; minus 1024 + z and 64 + z.  k ascending.
+struct CodesF16 {
+    typedef ActF16 Act;
+    static constexpr uint32_t kMask = 0x00F0000Fu, kMagic = 0x54006400u;
+    static __device__ __forceinline__ GroupConst group_const(uint2_t sc, uint32_t z)
+    {
+        GroupConst g;
+        group_scales(g, sc);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        // byte selectors of v_perm_b32: 0-3 pick from the second operand, 0x0c gives zero: byte e into both halves
-        const uint32_t u = __builtin_amdgcn_perm(w, w, 0x0C000C00u + 0x00010001u * (uint32_t)e);
-        H2 t;
-        t.u = (u & mask) | magic;
-        t.h = t.h + zv.h;
-        r.u[e] = t.u;
+        for (int c = 0; c < 4; ++c) g.negz[c] = (((z >> (4 * c)) & 15u) * 0x00100001u) | 0xD400E400u;  // sign | 64 or 1024 | z in the bits that count ones
+        return g;
     }
-    return r.h;
-}
+    static __device__ __forceinline__ ActF16::operand_t unpack(uint32_t w, uint32_t negz, uint32_t mask, uint32_t magic)
+    {
+        H2 zv;
+        zv.u = negz;
+        H8 r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            // byte selectors of v_perm_b32: 0-3 pick from the second operand, 0x0c gives zero: byte e into both halves
+            const uint32_t u = __builtin_amdgcn_perm(w, w, 0x0C000C00u + 0x00010001u * (uint32_t)e);
+            H2 t;
+            t.u = (u & mask) | magic;
+            t.h = t.h + zv.h;
+            r.u[e] = t.u;
+        }
+        return r.h;
+    }
+};
 
+// (BF16 activations stay with the eight-wave form: gfx950 has no packed BF16 add, and q - z through FP32 costs more
+// than that form's sum of x.)
+
+template <typename Codes>
 __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync, const int row_blocks, const int red_waves)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -149,33 +168,33 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
         vz += row_z;
     };
 
-    // ---- X: this wave's LDS (two chunk buffers), two register sets of chunks in flight ----
-    // kLanesPerRow neighbouring lanes fetch the 128 contiguous bytes a chunk takes of one row of X; load q of a lane:
-    // row q kRowsPerLoad + lane / kLanesPerRow, packed row lane % kLanesPerRow of the chunk.  X is staged as it is:
-    // the operand order of codes_minus_zero is the order of k.
-    unsigned char *wl = smem + (size_t)wave * kWaveBytes;
+    // ---- X: straight from global memory into this wave's LDS (four chunk buffers), no registers ----
+    // A wave-wide load into LDS puts lane l's 16 bytes at (base + 16 l): eight lanes fetch the 128 contiguous bytes a
+    // chunk takes of one row of X (eight packed rows), eight rows per load.  So that the MFMA's operand reads (sixteen
+    // consecutive rows, one packed row) do not all fall into the same banks, lane (row r, place x) fetches packed row
+    // x ^ r: within a row's 128 bytes the packed rows sit rotated by the row number.  X is staged as it is: the operand
+    // order of the unpack (CodesF16) is the order of k.
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(a.X), 0, (uint32_t)((size_t)a.M * a.K * 2), kRawBuffer);
-    uint32_t xg[kPerLane];
+    uint32_t xg[kLoadsPerChunk];
 #pragma unroll
-    for (int q = 0; q < kPerLane; ++q) {
-        const uint32_t m = (uint32_t)m0 + (uint32_t)(q * kRowsPerLoad + lane / kLanesPerRow);
-        const uint32_t prow = (uint32_t)g0 * 16u + (uint32_t)(lane % kLanesPerRow);
+    for (int q = 0; q < kLoadsPerChunk; ++q) {
+        const uint32_t rl = (uint32_t)lane >> 3, m = (uint32_t)m0 + (uint32_t)(8 * q) + rl;
+        const uint32_t prow = (uint32_t)g0 * 16u + (((uint32_t)lane & 7u) ^ rl);
         xg[q] = m < (uint32_t)a.M ? (m * (uint32_t)a.K + prow * 8u) * 2u : kOutOfRange;
     }
-    const uint32_t xl0 = (uint32_t)(((lane % kLanesPerRow) * kRowStride + lane / kLanesPerRow) * 16);
-    uint4_t xd[2][kPerLane];
-    const uint32_t nchunks = (uint32_t)ng * 2u;
-    auto x_load = [&](uint4_t(&d)[kPerLane], uint32_t chunk) {  // chunk of the wave's run (past it: out of range, zeros)
+    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+    auto x_fetch = [&](int buffer, uint32_t chunk) {  // chunk of the wave's run into LDS buffer `buffer` (past the run: other k, unused)
         const uint32_t so = chunk * (kChunkBlocks * kBlockRows * 16u);
 #pragma unroll
-        for (int q = 0; q < kPerLane; ++q) d[q] = __builtin_amdgcn_raw_buffer_load_b128(rx, chunk < nchunks ? xg[q] : kOutOfRange, so, 0);
+        for (int q = 0; q < kLoadsPerChunk; ++q)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(smem + (size_t)wave * kWaveBytes + buffer * kBufBytes + q * 1024), 16, xg[q], so, 0, 0);
     };
-    auto x_store = [&](const uint4_t(&d)[kPerLane], int par) {
+    // this lane's A entry of block lb of a chunk, row tile 0: row j of the tile = load j / 8, row j % 8 of it; packed row 4 lb + g4
+    uint32_t xa[kChunkBlocks];
 #pragma unroll
-        for (int q = 0; q < kPerLane; ++q)
-            *reinterpret_cast<uint4_t *>(wl + par * kBufBytes + xl0 + q * kRowsPerLoad * 16) = d[q];
-    };
+    for (int lb = 0; lb < kChunkBlocks; ++lb)
+        xa[lb] = (uint32_t)(wave * kWaveBytes + (j >> 3) * 1024 + (j & 7) * 128 + (((4 * lb + g4) ^ (j & 7)) * 16));
 
     float4_t tot[kRT][4];
 #pragma unroll
@@ -184,48 +203,53 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
         for (int c = 0; c < 4; ++c) tot[rt][c] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
     if (ng > 0) {
-        // X of the first two chunks and each group's scales go ahead of that group's weights: loads return in order
-        x_load(xd[0], 0);
-        x_load(xd[1], 1);
+        // X of the first chunk and each group's scales go ahead of that group's weights: loads return in order
+        x_fetch(0, 0);
 #pragma unroll
         for (int h = 0; h < kRing; ++h) {
             load_sz(h);
 #pragma unroll
             for (int p = 0; p < kBpg; ++p) load_w(wq[h * kBpg + p]);
+            if (h == 0) {
+                x_fetch(1, 1);
+                x_fetch(2, 2);
+                x_fetch(3, 3);
+            }
         }
-        x_store(xd[0], 0);
-        x_load(xd[0], 2);
-
-        const uint32_t xa0 = (uint32_t)(wave * kWaveBytes + (g4 * kRowStride + j) * 16);  // A entry of block 0, row tile 0, buffer 0
-        uint32_t mask = 0x00F0000Fu, magic = 0x54006400u;
+        uint32_t mask = Codes::kMask, magic = Codes::kMagic;
         asm volatile("" : "+v"(mask), "+v"(magic));  // kept in vector registers: v_and_or_b32 has no room for two constants
         const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
 
-        // operands of the block in use and of the next one; per-group sums of the group in use and of the one before
-        half8_t bop[2][4];
-        H8 xop[2][kRT];
-        float4_t part[2][kRT][4];
-        GroupConst gc = group_const(scq[0], (zwq[0] | zfill) >> zsh);
+        // operands of the block in use and of the next one; the sums of the group in use
+        typedef typename Codes::Act Act;
+        typename Act::operand_t bop[2][4];
+        uint4_t xop[2][kRT];
+        float4_t part[kRT][4];
+        GroupConst gc = Codes::group_const(scq[0], (zwq[0] | zfill) >> zsh);
         float s_prev[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int c = 0; c < 4; ++c) bop[0][c] = codes_minus_zero(wq[0][c], gc.negz[c], mask, magic);
+        for (int c = 0; c < 4; ++c) bop[0][c] = Codes::unpack(wq[0][c], gc.negz[c], mask, magic);
         load_sz(0);     // the same place, and its first block, kRing groups on (past the run: zeros, no traffic)
         load_w(wq[0]);
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) part[1][rt][c] = zero4;  // "the group before the first": nothing
+            for (int c = 0; c < 4; ++c) part[rt][c] = zero4;  // "the group before the first": nothing
+        // chunk 0 has landed when at most the operations asked for after it are on their way: the first group's scales,
+        // zero points and weights (6), 3 chunks of X (24), the second group's (6), the load_sz and load_w just above (3)
+        asm volatile("s_waitcnt vmcnt(39)" ::: "memory");
 #pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) xop[0][rt].u = *reinterpret_cast<const uint4_t *>(smem + xa0 + rt * 256);
+        for (int rt = 0; rt < kRT; ++rt) xop[0][rt] = *reinterpret_cast<const uint4_t *>(smem + xa[0] + rt * 2048);
 
-        // One group from ring place R.  Its chunk c sits in LDS buffer c.  Entering, bop[0] and xop[0] hold its first
-        // block, gc its constants, s_prev and part[(R + 1) & 1] the previous group's scales and sums.  Only this
+        // One group from ring place R.  Entering, bop[0] and xop[0] hold its first block, gc its constants, s_prev and
+        // part the previous group's scales and sums: Eq. 2's step for an output tile of the previous group,
+        // tot += s part, sits just ahead of the MFMA that starts the tile's sums of this group.  Only this
         // wave touches its LDS and the LDS operations of one wave complete in order; the fences only keep the
         // compiler from moving them across the staging.
         auto do_group = [&](auto place, const uint32_t gi) {
             constexpr int R = decltype(place)::value;
             constexpr int RN = (R + 1) % kRing;
-            constexpr int PC = R & 1, PP = PC ^ 1;  // sums of this group, of the previous one
+            constexpr int PC = R & 1, PP = PC ^ 1;  // parity of this group, of the next one: their chunks' LDS buffers
             float s_next[4];
 #pragma unroll
             for (int p = 0; p < kBpg; ++p) {
@@ -233,48 +257,53 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
                 // the next block's operands, independent of the MFMAs below
                 if (p + 1 < kBpg) {
 #pragma unroll
-                    for (int cc = 0; cc < 4; ++cc) bop[(p + 1) & 1][cc] = codes_minus_zero(wq[R * kBpg + p + 1][cc], gc.negz[cc], mask, magic);
+                    for (int cc = 0; cc < 4; ++cc) bop[(p + 1) & 1][cc] = Codes::unpack(wq[R * kBpg + p + 1][cc], gc.negz[cc], mask, magic);
                     load_w(wq[R * kBpg + p + 1]);  // the same block kRing groups on
                 } else {
 #pragma unroll
                     for (int cc = 0; cc < 4; ++cc) s_next[cc] = gc.s[cc];
-                    gc = group_const(scq[RN], (zwq[RN] | zfill) >> zsh);  // the next group's first block
+                    gc = Codes::group_const(scq[RN], (zwq[RN] | zfill) >> zsh);  // the next group's first block
 #pragma unroll
-                    for (int cc = 0; cc < 4; ++cc) bop[0][cc] = codes_minus_zero(wq[RN * kBpg][cc], gc.negz[cc], mask, magic);
+                    for (int cc = 0; cc < 4; ++cc) bop[0][cc] = Codes::unpack(wq[RN * kBpg][cc], gc.negz[cc], mask, magic);
                     load_sz(RN);
                     load_w(wq[RN * kBpg]);
                 }
-                if (lb == kChunkBlocks - 1) {
-                    // The chunk's last block is in registers (xop[p & 1]).  The chunk after it, asked for two chunks
-                    // ago, goes to the other buffer (last read a chunk ago), and the chunk after the next is asked for.
-                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                    x_store(xd[c ^ 1], c ^ 1);
-                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                    x_load(xd[c ^ 1], gi * 2 + c + 3);
-                }
-                // the next block's X operands: the other block of this chunk, or the first of the next chunk
+                // the next block's X operands: the other block of this chunk, or the first block of the next chunk, which
+                // must have landed by now
                 {
-                    const int pn = (p + 1) % kBpg, cn = pn / kChunkBlocks, lbn = pn % kChunkBlocks;
-                    const unsigned char *xb = smem + xa0 + cn * kBufBytes + lbn * (kBlockRows * kRowStride * 16);
+                    const int pn = (p + 1) % kBpg, lbn = pn % kChunkBlocks;
+                    const int bn = p + 1 < kBpg ? 2 * PC + pn / kChunkBlocks : 2 * PP;  // its chunk's LDS buffer
+                    if (lb == kChunkBlocks - 1) {
+                        if (c == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kWaitChunk1) : "memory");
+                        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kWaitChunk0) : "memory");
+                    }
+                    const unsigned char *xb = smem + xa[lbn] + bn * kBufBytes;
 #pragma unroll
-                    for (int rt = 0; rt < kRT; ++rt) xop[(p + 1) & 1][rt].u = *reinterpret_cast<const uint4_t *>(xb + rt * 256);
+                    for (int rt = 0; rt < kRT; ++rt) xop[(p + 1) & 1][rt] = *reinterpret_cast<const uint4_t *>(xb + rt * 2048);
                 }
-                // this block's MFMAs
+                // this block's MFMAs; ahead of the group's first ones the previous group's step
 #pragma unroll
                 for (int rt = 0; rt < kRT; ++rt)
 #pragma unroll
-                    for (int cc = 0; cc < 4; ++cc)
-                        part[PC][rt][cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xop[p & 1][rt].h, bop[p & 1][cc], p == 0 ? zero4 : part[PC][rt][cc], 0, 0, 0);
-                // Eq. 2's step for a quarter of the previous group: its row tile p
+                    for (int cc = 0; cc < 4; ++cc) {
+                        if (p == 0) {
 #pragma unroll
-                for (int cc = 0; cc < 4; ++cc)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) tot[p][cc][i] = __builtin_fmaf(s_prev[cc], part[PP][p][cc][i], tot[p][cc][i]);
-                // the schedule of the block: every MFMA followed by its share of the vector instructions around it
+                            for (int i = 0; i < 4; ++i) tot[rt][cc][i] = __builtin_fmaf(s_prev[cc], part[rt][cc][i], tot[rt][cc][i]);
+                        }
+                        part[rt][cc] = Act::mfma(Act::x_operand(xop[p & 1][rt]), bop[p & 1][cc], p == 0 ? zero4 : part[rt][cc]);
+                    }
+                // the schedule of the block: every MFMA with its share of the vector instructions around it
 #pragma unroll
                 for (int i = 0; i < 4 * kRT; ++i) {
+                    if (p == 0) __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                }
+                if (lb == kChunkBlocks - 1) {
+                    // This chunk's last block is in registers (xop[p & 1]) and its MFMAs are issued: its buffer takes
+                    // the chunk four chunks on.  (The barrier keeps the compiler from moving the fetch above them.)
+                    asm volatile("" ::: "memory");
+                    x_fetch(2 * PC + c, gi * 2 + c + 4);
                 }
             }
 #pragma unroll
@@ -284,18 +313,17 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
         for (uint32_t gi = 0; gi < (uint32_t)ng; gi += kRing) {
             do_group(std::integral_constant<int, 0>{}, gi);
             if (gi + 1 < (uint32_t)ng) do_group(std::integral_constant<int, 1>{}, gi + 1);
-            if (gi + 2 < (uint32_t)ng) do_group(std::integral_constant<int, 2>{}, gi + 2);
-            if (gi + 3 < (uint32_t)ng) do_group(std::integral_constant<int, 3>{}, gi + 3);
         }
+        // the fetches past the run's end write into this wave's LDS too: they must have landed before the final sums
+        // reuse the space
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         // the last group's step
-        const int last = (ng - 1) & 1;
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt)
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    tot[rt][cc][i] = __builtin_fmaf(s_prev[cc], (last ? part[1][rt][cc][i] : part[0][rt][cc][i]), tot[rt][cc][i]);
+                for (int i = 0; i < 4; ++i) tot[rt][cc][i] = __builtin_fmaf(s_prev[cc], part[rt][cc][i], tot[rt][cc][i]);
     }
 
     // Phase 3 inside the workgroup, then across workgroups (see w4a16_finish.h).  The sums are regrouped
@@ -312,9 +340,9 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
             for (int i = 0; i < 4; ++i) mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = mine4[rt][i];
     };
     if (finish == kFinishAccumulator)
-        reduce_and_finish<ActF16, kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+        reduce_and_finish<typename Codes::Act, kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
     else
-        reduce_and_finish<ActF16, kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+        reduce_and_finish<typename Codes::Act, kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
 }
 
 }  // namespace
@@ -335,11 +363,9 @@ hipError_t launch_tile_wide(const GemmArgs &a, int finish, unsigned long long *s
     const int row_blocks = (a.M + kRowsX - 1) / kRowsX;
     const long long grid = ((long long)ntiles * a.split + kXcds - 1) / kXcds * kXcds * row_blocks;
     if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
-    if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(tile_wide_kernel, dim3((unsigned)grid), dim3(64 * kWaves), lds, stream, a, finish, sync, row_blocks, red_waves);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_wide_kernel<CodesF16>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  // beyond the default dynamic-LDS allowance
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(tile_wide_kernel<CodesF16>, dim3((unsigned)grid), dim3(64 * kWaves), lds, stream, a, finish, sync, row_blocks, red_waves);
     return hipGetLastError();
 }
 

@@ -89,35 +89,32 @@ def test_small_shapes_every_split(gpu, M, K, N, group):
             assert r <= 1.0, (M, K, N, group, kernel, split, r)
 
 
-@pytest.mark.parametrize("deq", [0, 1, 2])
+@pytest.mark.parametrize("form", ["scheduler", "eight waves at 64 rows"])
 @pytest.mark.parametrize("rows_x", [16, 32, 64])
-def test_tile_family_every_row_block(gpu, rows_x, deq):
-    """The TILE kernels for 16, 32 and 64 rows of X per workgroup: the scheduler's forms (at 64 rows and group = 128 four
-    waves per workgroup with q - z as the operand), the opt-in form with weights dequantized to FP16 in registers
-    (deq = 1), and the eight-wave form at 64 rows (deq = 2).  The scheduler takes the larger blocks
-    only where N is large, so the library's tuning knobs force them here on small ragged shapes
-    (rows past M, columns past N, fewer groups than waves, group sizes with and without the
-    group-aligned loop)."""
+def test_tile_family_every_row_block(gpu, rows_x, form):
+    """The TILE kernels for 16, 32 and 64 rows of X per workgroup (at 64 rows and group = 128: four waves per workgroup
+    with q - z as the operand, and the eight-wave form with bare codes).  The scheduler takes the larger blocks only
+    where N is large, so the library's tuning knobs force them here on small ragged shapes (rows past M, columns past N,
+    fewer groups than waves, group sizes with and without the group-aligned loop)."""
     _, binding = gpu
-    if deq == 2 and rows_x != 64:
+    eight = form != "scheduler"
+    if eight and rows_x != 64:
         pytest.skip("the four-wave form exists at 64 rows only")
     binding.tune("tile_rows", rows_x)
-    binding.tune("tile_deq", 1 if deq == 1 else 0)
-    binding.tune("tile_wide", 2 if deq == 2 else 0)  # deq == 2: the eight-wave form at 64 rows instead of the four-wave one
+    binding.tune("tile_wide", 2 if eight else 0)
     binding.tune("tile_dyn", 2)  # not the ticket form, which 16 rows would take
     try:
         _tile_rows_cases(gpu, rows_x)
     finally:
         binding.tune("tile_rows", 0)
-        binding.tune("tile_deq", 0)
         binding.tune("tile_wide", 0)
         binding.tune("tile_dyn", 0)
 
 
-def test_dequantized_operand_form_is_exact_where_fp16_holds_the_weights(gpu):
-    """The opt-in many-row TILE form (knob tile_deq) rounds s (q - z) to FP16 once (Algorithm 1, Phase 1).  With power-of-two scales that
-    rounding is exact, and with small integers in X so is every sum: the result must be the oracle's, bit for bit;
-    with one-hot rows of X the result is the FP16 rounding of the weight row itself."""
+def test_four_wave_form_exact_sums_and_one_hot_rows(gpu):
+    """The four-wave TILE form multiplies X with q - z as exact FP16 integers and applies s per group in FP32.  With
+    power-of-two scales and small integers in X every sum is exact: the result must be the oracle's, bit for bit; with
+    one-hot rows of X the result is the FP16 rounding of the weight row itself."""
     torch, binding = gpu
     rng = np.random.default_rng(23)
     M, K, N, group = 70, 1024, 264, 128
@@ -126,27 +123,22 @@ def test_dequantized_operand_form_is_exact_where_fp16_holds_the_weights(gpu):
     s = (2.0 ** rng.integers(-8, -3, (G, N))).astype(np.float16)
     X = rng.integers(-3, 4, (M, K)).astype(np.float16)
     ref = orc.gemm(X, Wp, s, Zp, group)
-    binding.tune("tile_deq", 1)
-    binding.tune("tile_dyn", 2)
+    binding.tune("tile_rows", 64)
     try:
-        for rows_x in (16, 32, 64):
-            binding.tune("tile_rows", rows_x)
-            for split in (1, 3):
-                say("deq exact", rows_x, split)
-                Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=binding.KERNEL_TILE, split=split)
-                assert np.array_equal(Y, orc.to_fp16(ref)), (rows_x, split)
+        for split in (1, 3, 8):
+            say("four waves exact", split)
+            assert binding.query_plan(M, N, K, group, binding.KERNEL_TILE, split)["waves_k"] == 4
+            Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=binding.KERNEL_TILE, split=split)
+            assert np.array_equal(Y, orc.to_fp16(ref)), split
         X1, Wp1, s1, Zp1 = wl.make(64, K, N, index=2301, group=group)
         X1[:] = 0
         ks = rng.choice(K, size=64, replace=False)
         X1[np.arange(64), ks] = 1
-        say("deq one-hot")
-        binding.tune("tile_rows", 64)
+        say("four waves one-hot")
         Y = run_gpu(gpu, X1, Wp1, s1, Zp1, group, kernel=binding.KERNEL_TILE, split=1)
         assert np.array_equal(Y, orc.dequant(Wp1, s1, Zp1, group)[ks].astype(np.float16))
     finally:
         binding.tune("tile_rows", 0)
-        binding.tune("tile_deq", 0)
-        binding.tune("tile_dyn", 0)
 
 
 def _tile_rows_cases(gpu, rows_x):
