@@ -84,7 +84,7 @@ typedef enum {
                                     share the slice (exact sums in LDS); slices of different workgroups meet in a
                                     64-bit fixed-point accumulator by one atomic add each, no second launch        */
     W4A16_KERNEL_TILE = 4        /* any M, the scheduler's choice otherwise: 64-column tile x 16, 32 or 64 rows of X
-                                    per workgroup, its waves (eight; four at 64 rows) own contiguous runs of K (LDS
+                                    per workgroup, its waves (eight; four at 32 and 64 rows, group 128) own contiguous runs of K (LDS
                                     reduction), plain MFMA operand layout; slices of different workgroups meet as
                                     in STRIPE                                                                         */
 } w4a16_kernel;
@@ -228,8 +228,8 @@ int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, 
  *   "tile_dyn"       16 rows of X per workgroup: 1 = units of K always handed out by ticket, 2 = never
  *   "tile_depth"     units in flight per wave of that form (1, 2)
  *   "tile_waves"     waves per TILE workgroup (4..8)
- *   "tile_wide"      2: TILE at 64 rows of X per workgroup, FP16, group 128: the eight-wave form instead of the
- *                    four-wave one
+ *   "tile_wide"      2: TILE at 32 or 64 rows of X per workgroup, FP16, group 128: the eight-wave form instead of
+ *                    the four-wave one
  *   "log"            1: every w4a16_gemm* call prints its plan on stderr (the one case in which the library prints)
  * Returns W4A16_ERR_UNSUPPORTED for an unknown knob.
  */

@@ -63,7 +63,7 @@ struct Tuning {
     int tile_dyn = 0;       // 16 rows of X per workgroup: 1 = units always handed out by ticket, 2 = never (equal runs per wave)
     int tile_depth = 0;     // units in flight per wave of the ticket form (1, 2)
     int tile_waves = 0;     // waves per TILE workgroup (4..8)
-    int tile_wide = 0;      // TILE at 64 rows of X per workgroup, FP16, group 128: 2 = the eight-wave form instead of the four-wave one
+    int tile_wide = 0;      // TILE at 32 or 64 rows of X per workgroup, FP16, group 128: 2 = the eight-wave form instead of the four-wave one
     int log = 0;            // 1: every call prints its plan on stderr
 };
 
@@ -193,7 +193,7 @@ bool tile_by_ticket(int M, int rows_x) { return rows_x == 16 && (tuning().tile_d
 
 // TILE at 64 rows of X per workgroup and group = 128: four waves per workgroup, each alone on its SIMD
 // (w4a16_tile_wide.hip; FP16 only: BF16 activations run such a plan with the eight-wave form).
-bool tile_wide(int rows_x, int group) { return rows_x == 64 && group == 128 && tuning().tile_wide != 2; }
+bool tile_wide(int rows_x, int group) { return (rows_x == 64 || rows_x == 32) && group == 128 && tuning().tile_wide != 2; }
 
 // LDS a STRIPE workgroup needs for a slice of gps groups, and the most it may use.
 size_t stripe_lds(int M, int group, int gps, int waves)
@@ -490,7 +490,7 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
         e = launch_tile_dyn(a, finish, b.sync, plan.waves_k, tuning().tile_depth == 2 && !bf16 ? 2 : 1, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE && tile_wide(plan.tile_m, group) && !bf16) {
         // four waves with the whole register file each; measured on M = 128, K = N = 8192: 27.5 us against 33.1 us with eight
-        e = launch_tile_wide(a, finish, b.sync, st);
+        e = launch_tile_wide(a, finish, b.sync, plan.tile_m, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE) {
         e = launch_tile(a, finish, b.sync, plan.tile_m, tile_wide(plan.tile_m, group) ? 8 : plan.waves_k, st);
     } else {

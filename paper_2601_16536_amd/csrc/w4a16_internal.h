@@ -62,8 +62,8 @@ int stripe_dyn_lds_limit();                                           // most it
 // workgroup, `waves` (4..8) waves per workgroup that split the K slice; `finish` and `sync` as in the STRIPE
 // family.
 hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, int waves, hipStream_t stream);
-// TILE family at 64 rows of X per workgroup, FP16, group = 128: four waves per workgroup (w4a16_tile_wide.hip).
-hipError_t launch_tile_wide(const GemmArgs &a, int finish, unsigned long long *sync, hipStream_t stream);
+// TILE family at 64 or 32 rows of X per workgroup, FP16, group = 128: four waves per workgroup (w4a16_tile_wide.hip).
+hipError_t launch_tile_wide(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, hipStream_t stream);
 // TILE family, 16 rows of X per workgroup, the slice handed out to the waves by ticket (w4a16_tile_dyn.hip); `depth` (1, 2)
 // units in flight per wave.
 hipError_t launch_tile_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int depth, hipStream_t stream);

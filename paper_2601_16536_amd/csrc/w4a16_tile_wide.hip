@@ -1,5 +1,6 @@
-// W4A16 multiply, TILE family at 64 rows of X per workgroup (M > 32 on wide matrices), FP16, group = 128: one workgroup
-// of FOUR waves per (64-column tile, 64 rows of X, K slice), each wave alone on its SIMD with the whole register file.
+// W4A16 multiply, TILE family at 64 or 32 rows of X per workgroup (M > 16 on wide matrices), FP16, group = 128: one
+// workgroup of FOUR waves per (64-column tile, 16 RT rows of X, K slice), each wave alone on its SIMD with the whole
+// register file.
 //
 // Why this form.  At 64 rows a wave issues 16 MFMAs 16x16x32 per block of 32 k, and what bounds the kernel is
 // instruction issue (measured on M = 128, K = N = 8192): a vector instruction costs a wave 4 cycles, an MFMA 8 when
@@ -26,26 +27,38 @@ namespace w4a16 {
 namespace {
 
 constexpr int kTileCols = 64;
-constexpr int kRowsX = 64;
-constexpr int kRT = 4;          // row tiles of 16
 constexpr int kBlockRows = 4;   // packed rows per block: one MFMA step of 32 k
 constexpr int kBpg = 4;         // blocks per group (group = 128)
 constexpr int kXcds = 8;
 constexpr int kWaves = 4;
 constexpr int kRing = 2;        // groups of weights in flight per wave (registers): eight blocks, about 3 us, ahead
 constexpr int kChunkBlocks = 2; // blocks per staged chunk of X: whole 128-byte lines of a row
-constexpr int kLoadsPerChunk = 8;                // wave-wide loads per chunk: eight rows of X each, 1 KiB
-constexpr int kBufBytes = kLoadsPerChunk * 1024; // a chunk in LDS: 64 rows x 128 bytes, no padding
-constexpr int kBuffers = 4;                      // chunks of X per wave in LDS: the one in use and three on their way
-constexpr int kWaveBytes = kBuffers * kBufBytes;
-// Vector-memory operations a wave issues per group, in program order (see do_group):
-//   block 0: W; block 1: W, X x 8; block 2: W; block 3: scales, zero points, W, X x 8.
-// The compiler does not know that the loads into LDS must have landed before the LDS reads that use them: the waits
-// are written by hand, as the number of operations that may still be on their way (loads return in order).
-constexpr int kWaitChunk1 = 24;  // at block 1, for the group's second chunk, asked for at block 3 two groups ago: one whole
-                                 // group (22) + W + W since then
-constexpr int kWaitChunk0 = 26;  // at block 3, for the next group's first chunk, asked for at block 1 of the group before:
-                                 // W, scales, zero points, W, X x 8 (12) + W, W, X x 8, W, scales, zero points, W (14)
+constexpr int kBuffers = 4;     // chunks of X per wave in LDS: the one in use and three on their way
+
+// Sizes that depend on the rows of X per workgroup, and the hand-written waits.  The compiler does not know that the
+// loads into LDS must have landed before the LDS reads that use them: the waits are written by hand, as the number of
+// vector-memory operations that may still be on their way (loads return to a wave in the order it asked).  Per group
+// a wave issues, in program order (see do_group), with X = kLoadsPerChunk:
+//   block 0: W; block 1: W, X loads into LDS; block 2: W; block 3: scales, zero points, W, X loads into LDS.
+template <int RT>
+struct Wide {
+    static constexpr int kRowsX = 16 * RT;
+    static constexpr int kLoadsPerChunk = 2 * RT;              // wave-wide loads per chunk: eight rows of X each, 1 KiB
+    static constexpr int kBufBytes = kLoadsPerChunk * 1024;    // a chunk in LDS: rows x 128 bytes, no padding
+    static constexpr int kWaveBytes = kBuffers * kBufBytes;
+    static constexpr int kPerGroup = 4 + 2 + 2 * kLoadsPerChunk;
+    // at block 1, for the group's second chunk, asked for at block 3 two groups ago: one whole group + W + W since then
+    static constexpr int kWaitChunk1 = kPerGroup + 2;
+    // at block 3, for the next group's first chunk, asked for at block 1 of the group before: W, scales, zero points, W,
+    // X loads; then W, W, X loads, W, scales, zero points, W
+    static constexpr int kWaitChunk0 = (4 + kLoadsPerChunk) + (6 + kLoadsPerChunk);
+    // at the start, for the first chunk: the first group's scales, zero points and weights (6), three chunks of X, the
+    // second group's (6), and the first refill (3) were asked for after it
+    static constexpr int kWaitFirst = 15 + 3 * kLoadsPerChunk;
+    // vector instructions the schedule puts ahead of every MFMA: 48 per block for the next block's operands, and in a
+    // group's first block 16 RT more for the step of the group before
+    static constexpr int kValuFirst = RT == 4 ? 7 : 11, kValu = RT == 4 ? 3 : 6;
+};
 
 // The B operand q - z, exact in either 16-bit format, and what it takes per group: for the four columns of a lane the
 // pair to subtract and the scale as a float.
@@ -99,10 +112,21 @@ struct CodesF16 {
 // (BF16 activations stay with the eight-wave form: gfx950 has no packed BF16 add, and q - z through FP32 costs more
 // than that form's sum of x.)
 
-template <typename Codes>
+// A chunk of X into LDS: each wave-wide load puts lane l's 16 bytes at (base + 16 l), 1 KiB per load.
+template <int LOADS>
+__device__ __forceinline__ void fetch_chunk(__amdgpu_buffer_rsrc_t rx, unsigned char *base, const uint32_t (&xg)[LOADS], uint32_t so)
+{
+    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+#pragma unroll
+    for (int q = 0; q < LOADS; ++q) __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(base + q * 1024), 16, xg[q], so, 0, 0);
+}
+
+template <typename Codes, int RT>
 __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync, const int row_blocks, const int red_waves)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    typedef Wide<RT> Sh;
+    constexpr int kRT = RT, kRowsX = Sh::kRowsX, kLoadsPerChunk = Sh::kLoadsPerChunk, kBufBytes = Sh::kBufBytes, kWaveBytes = Sh::kWaveBytes;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -183,12 +207,12 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
         const uint32_t prow = (uint32_t)g0 * 16u + (((uint32_t)lane & 7u) ^ rl);
         xg[q] = m < (uint32_t)a.M ? (m * (uint32_t)a.K + prow * 8u) * 2u : kOutOfRange;
     }
-    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+    // The fences keep the compiler from moving other memory operations across the fetch: the hand-written waits
+    // count the loads asked for after it, and the LDS reads of the buffer it refills must stay ahead of it.
     auto x_fetch = [&](int buffer, uint32_t chunk) {  // chunk of the wave's run into LDS buffer `buffer` (past the run: other k, unused)
-        const uint32_t so = chunk * (kChunkBlocks * kBlockRows * 16u);
-#pragma unroll
-        for (int q = 0; q < kLoadsPerChunk; ++q)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(smem + (size_t)wave * kWaveBytes + buffer * kBufBytes + q * 1024), 16, xg[q], so, 0, 0);
+        asm volatile("" ::: "memory");
+        fetch_chunk<kLoadsPerChunk>(rx, smem + (size_t)wave * kWaveBytes + buffer * kBufBytes, xg, chunk * (kChunkBlocks * kBlockRows * 16u));
+        asm volatile("" ::: "memory");
     };
     // this lane's A entry of block lb of a chunk, row tile 0: row j of the tile = load j / 8, row j % 8 of it; packed row 4 lb + g4
     uint32_t xa[kChunkBlocks];
@@ -235,9 +259,8 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
         for (int rt = 0; rt < kRT; ++rt)
 #pragma unroll
             for (int c = 0; c < 4; ++c) part[rt][c] = zero4;  // "the group before the first": nothing
-        // chunk 0 has landed when at most the operations asked for after it are on their way: the first group's scales,
-        // zero points and weights (6), 3 chunks of X (24), the second group's (6), the load_sz and load_w just above (3)
-        asm volatile("s_waitcnt vmcnt(39)" ::: "memory");
+        // chunk 0 has landed when at most the operations asked for after it are on their way
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(Sh::kWaitFirst) : "memory");
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) xop[0][rt] = *reinterpret_cast<const uint4_t *>(smem + xa[0] + rt * 2048);
 
@@ -274,8 +297,8 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
                     const int pn = (p + 1) % kBpg, lbn = pn % kChunkBlocks;
                     const int bn = p + 1 < kBpg ? 2 * PC + pn / kChunkBlocks : 2 * PP;  // its chunk's LDS buffer
                     if (lb == kChunkBlocks - 1) {
-                        if (c == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kWaitChunk1) : "memory");
-                        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kWaitChunk0) : "memory");
+                        if (c == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(Sh::kWaitChunk1) : "memory");
+                        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(Sh::kWaitChunk0) : "memory");
                     }
                     const unsigned char *xb = smem + xa[lbn] + bn * kBufBytes;
 #pragma unroll
@@ -295,14 +318,12 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
                 // the schedule of the block: every MFMA with its share of the vector instructions around it
 #pragma unroll
                 for (int i = 0; i < 4 * kRT; ++i) {
-                    if (p == 0) __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
-                    else __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                    if (p == 0) __builtin_amdgcn_sched_group_barrier(0x002, Sh::kValuFirst, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x002, Sh::kValu, 0);
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 }
                 if (lb == kChunkBlocks - 1) {
-                    // This chunk's last block is in registers (xop[p & 1]) and its MFMAs are issued: its buffer takes
-                    // the chunk four chunks on.  (The barrier keeps the compiler from moving the fetch above them.)
-                    asm volatile("" ::: "memory");
+                    // This chunk's last block is in registers (xop[p & 1]): its buffer takes the chunk four chunks on.
                     x_fetch(2 * PC + c, gi * 2 + c + 4);
                 }
             }
@@ -345,28 +366,34 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
         reduce_and_finish<typename Codes::Act, kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
 }
 
+template <int RT>
+hipError_t launch_rt(const GemmArgs &a, int finish, unsigned long long *sync, hipStream_t stream)
+{
+    typedef Wide<RT> Sh;
+    const size_t stage = (size_t)kWaves * Sh::kWaveBytes;
+    const size_t one = (size_t)Sh::kRowsX * kTileCols * 4;  // a wave's result tile in fp32: the final sums reuse the space
+    const size_t red = one * kWaves;
+    const size_t lds = stage > red ? stage : red;
+    const int ntiles = (a.N + kTileCols - 1) / kTileCols;
+    const int row_blocks = (a.M + Sh::kRowsX - 1) / Sh::kRowsX;
+    const long long grid = ((long long)ntiles * a.split + kXcds - 1) / kXcds * kXcds * row_blocks;
+    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_wide_kernel<CodesF16, RT>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  // beyond the default dynamic-LDS allowance
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((tile_wide_kernel<CodesF16, RT>), dim3((unsigned)grid), dim3(64 * kWaves), lds, stream, a, finish, sync, row_blocks, kWaves);
+    return hipGetLastError();
+}
+
 }  // namespace
 
-hipError_t launch_tile_wide(const GemmArgs &a, int finish, unsigned long long *sync, hipStream_t stream)
+hipError_t launch_tile_wide(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, hipStream_t stream)
 {
-    if (a.group != 128 || a.bf16) return hipErrorInvalidValue;
+    if (a.group != 128 || a.bf16 || (rows_x != 32 && rows_x != 64)) return hipErrorInvalidValue;
     if (!finish_args_ok(a, finish, sync)) return hipErrorInvalidValue;
     const unsigned long long rows = (unsigned long long)a.groups_per_split * (a.group / 8);
     if (rows * a.N * 4ull >= 0x7F000000ull) return hipErrorInvalidValue;  // slice-relative 32-bit buffer offsets
     if ((unsigned long long)a.M * a.K * 2ull >= 0x7F000000ull) return hipErrorInvalidValue;
-    const size_t stage = (size_t)kWaves * kWaveBytes;
-    const size_t one = (size_t)kRowsX * kTileCols * 4;  // a wave's result tile in fp32: the final sums reuse the space
-    const size_t red = one * kWaves;
-    const size_t lds = stage > red ? stage : red;
-    const int red_waves = kWaves;
-    const int ntiles = (a.N + kTileCols - 1) / kTileCols;
-    const int row_blocks = (a.M + kRowsX - 1) / kRowsX;
-    const long long grid = ((long long)ntiles * a.split + kXcds - 1) / kXcds * kXcds * row_blocks;
-    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_wide_kernel<CodesF16>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  // beyond the default dynamic-LDS allowance
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(tile_wide_kernel<CodesF16>, dim3((unsigned)grid), dim3(64 * kWaves), lds, stream, a, finish, sync, row_blocks, red_waves);
-    return hipGetLastError();
+    return rows_x == 64 ? launch_rt<4>(a, finish, sync, stream) : launch_rt<2>(a, finish, sync, stream);
 }
 
 }  // namespace w4a16

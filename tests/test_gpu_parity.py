@@ -89,17 +89,17 @@ def test_small_shapes_every_split(gpu, M, K, N, group):
             assert r <= 1.0, (M, K, N, group, kernel, split, r)
 
 
-@pytest.mark.parametrize("form", ["scheduler", "eight waves at 64 rows"])
+@pytest.mark.parametrize("form", ["scheduler", "eight waves at 32 and 64 rows"])
 @pytest.mark.parametrize("rows_x", [16, 32, 64])
 def test_tile_family_every_row_block(gpu, rows_x, form):
-    """The TILE kernels for 16, 32 and 64 rows of X per workgroup (at 64 rows and group = 128: four waves per workgroup
-    with q - z as the operand, and the eight-wave form with bare codes).  The scheduler takes the larger blocks only
+    """The TILE kernels for 16, 32 and 64 rows of X per workgroup (at 32 and 64 rows and group = 128: four waves per
+    workgroup with q - z as the operand, and the eight-wave form with bare codes).  The scheduler takes the larger blocks only
     where N is large, so the library's tuning knobs force them here on small ragged shapes (rows past M, columns past N,
     fewer groups than waves, group sizes with and without the group-aligned loop)."""
     _, binding = gpu
     eight = form != "scheduler"
-    if eight and rows_x != 64:
-        pytest.skip("the four-wave form exists at 64 rows only")
+    if eight and rows_x == 16:
+        pytest.skip("the four-wave form exists at 32 and 64 rows only")
     binding.tune("tile_rows", rows_x)
     binding.tune("tile_wide", 2 if eight else 0)
     binding.tune("tile_dyn", 2)  # not the ticket form, which 16 rows would take
@@ -123,20 +123,21 @@ def test_four_wave_form_exact_sums_and_one_hot_rows(gpu):
     s = (2.0 ** rng.integers(-8, -3, (G, N))).astype(np.float16)
     X = rng.integers(-3, 4, (M, K)).astype(np.float16)
     ref = orc.gemm(X, Wp, s, Zp, group)
-    binding.tune("tile_rows", 64)
+    X1, Wp1, s1, Zp1 = wl.make(64, K, N, index=2301, group=group)
+    X1[:] = 0
+    ks = rng.choice(K, size=64, replace=False)
+    X1[np.arange(64), ks] = 1
     try:
-        for split in (1, 3, 8):
-            say("four waves exact", split)
-            assert binding.query_plan(M, N, K, group, binding.KERNEL_TILE, split)["waves_k"] == 4
-            Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=binding.KERNEL_TILE, split=split)
-            assert np.array_equal(Y, orc.to_fp16(ref)), split
-        X1, Wp1, s1, Zp1 = wl.make(64, K, N, index=2301, group=group)
-        X1[:] = 0
-        ks = rng.choice(K, size=64, replace=False)
-        X1[np.arange(64), ks] = 1
-        say("four waves one-hot")
-        Y = run_gpu(gpu, X1, Wp1, s1, Zp1, group, kernel=binding.KERNEL_TILE, split=1)
-        assert np.array_equal(Y, orc.dequant(Wp1, s1, Zp1, group)[ks].astype(np.float16))
+        for rows_x in (32, 64):
+            binding.tune("tile_rows", rows_x)
+            for split in (1, 3, 8):
+                say("four waves exact", rows_x, split)
+                assert binding.query_plan(M, N, K, group, binding.KERNEL_TILE, split)["waves_k"] == 4
+                Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=binding.KERNEL_TILE, split=split)
+                assert np.array_equal(Y, orc.to_fp16(ref)), (rows_x, split)
+            say("four waves one-hot", rows_x)
+            Y = run_gpu(gpu, X1, Wp1, s1, Zp1, group, kernel=binding.KERNEL_TILE, split=1)
+            assert np.array_equal(Y, orc.dequant(Wp1, s1, Zp1, group)[ks].astype(np.float16)), rows_x
     finally:
         binding.tune("tile_rows", 0)
 

@@ -123,8 +123,8 @@ def test_plans_are_well_formed(binding, M, N, K):
                 assert p["threads"] == 64 * p["waves_k"] and p["tile_n"] == 256
             elif p["kernel"] == binding.KERNEL_TILE:
                 assert p["tile_n"] == 64 and p["tile_m"] in (16, 32, 64)
-                # 64 rows of X per workgroup (group 128): four waves, each alone on its SIMD; else eight
-                assert (p["threads"], p["waves_k"]) == ((256, 4) if p["tile_m"] == 64 else (512, 8))
+                # 32 or 64 rows of X per workgroup (group 128): four waves; else eight
+                assert (p["threads"], p["waves_k"]) == ((256, 4) if p["tile_m"] in (32, 64) else (512, 8))
             else:
                 assert p["threads"] == 1024 and p["waves_k"] == 16
     assert binding.workspace_bytes(M, N, K, 128) >= binding.query_plan(M, N, K, 128)["workspace_bytes"]
