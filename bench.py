@@ -45,7 +45,7 @@ def kernel_name(plan, M, group):
         if plan["tile_m"] == 16 and M <= 16:
             return "tile_dyn_kernel"
         if group == 128:
-            return "tile_wide_kernel" if plan["tile_m"] in (32, 64) else "tile_group_kernel"
+            return "tile_wide_kernel" if plan["waves_k"] == 4 and plan["tile_m"] in (32, 64) else "tile_group_kernel"
     return KERNEL_NAMES.get(plan["kernel"], "?")
 
 
