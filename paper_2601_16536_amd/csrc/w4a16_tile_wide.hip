@@ -1,6 +1,6 @@
 // W4A16 multiply, TILE family at 64 or 32 rows of X per workgroup (M > 16 on wide matrices), FP16, group = 128: one
-// workgroup of FOUR waves per (64-column tile, 16 RT rows of X, K slice), each wave alone on its SIMD with the whole
-// register file.
+// workgroup of FOUR waves per (64-column tile, 16 RT rows of X, K slice); at 64 rows each wave is alone on its SIMD
+// with the whole register file.
 //
 // Why this form.  At 64 rows a wave issues 16 MFMAs 16x16x32 per block of 32 k, and what bounds the kernel is
 // instruction issue (measured on M = 128, K = N = 8192): a vector instruction costs a wave 4 cycles, an MFMA 8 when
@@ -37,7 +37,8 @@ constexpr int kBuffers = 4;     // chunks of X per wave in LDS: the one in use a
 
 // Sizes that depend on the rows of X per workgroup, and the hand-written waits.  The compiler does not know that the
 // loads into LDS must have landed before the LDS reads that use them: the waits are written by hand, as the number of
-// vector-memory operations that may still be on their way (loads return to a wave in the order it asked).  Per group
+// vector-memory operations that may still be on their way (loads return to a wave in the order it asked); compiler
+// fences around every fetch (x_fetch) keep the emitted order of the loads equal to the one counted here.  Per group
 // a wave issues, in program order (see do_group), with X = kLoadsPerChunk:
 //   block 0: W; block 1: W, X loads into LDS; block 2: W; block 3: scales, zero points, W, X loads into LDS.
 template <int RT>
