@@ -487,7 +487,7 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
     } else if (plan.kernel == W4A16_KERNEL_STRIPE) {
         e = launch_stripe(a, finish, b.sync, plan.waves_k, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE && tile_by_ticket(M, plan.tile_m)) {
-        e = launch_tile_dyn(a, finish, b.sync, plan.waves_k, tuning().tile_depth == 2 && !bf16 ? 2 : 1, st);
+        e = launch_tile_dyn(a, finish, b.sync, plan.waves_k, tuning().tile_depth == 2 && !bf16 && plan.waves_k <= 8 ? 2 : 1, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE && tile_wide(plan.tile_m, group) && !bf16) {
         // four waves with the whole register file each; measured on M = 128, K = N = 8192: 27.5 us against 33.1 us with eight
         e = launch_tile_wide(a, finish, b.sync, plan.tile_m, st);

@@ -37,8 +37,9 @@ constexpr uint32_t kLdsX = kLdsAcc + kRowsX * kTileCols * 8;
 template <int UB>
 constexpr uint32_t unit_x_bytes() { return UB * kBlockRows * kRowStride * 16; }
 
-template <typename Act, int UB, int D>
-__global__ __launch_bounds__(1024) void tile_dyn_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync)
+// BOUND: the most threads of a workgroup (the registers a wave may use follow from it: 128 at 1024, 256 at 512).
+template <typename Act, int UB, int D, int BOUND>
+__global__ __launch_bounds__(BOUND) void tile_dyn_kernel(const GemmArgs a, const int finish, unsigned long long *__restrict__ sync)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x;
@@ -214,18 +215,27 @@ __global__ __launch_bounds__(1024) void tile_dyn_kernel(const GemmArgs a, const 
     }
 }
 
-template <typename Act, int UB, int D>
-hipError_t launch_ud(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
+template <typename Act, int UB, int D, int BOUND>
+hipError_t launch_udb(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
 {
     const size_t lds = kLdsX + (size_t)waves * unit_x_bytes<UB>();
     const int ntiles = (a.N + kTileCols - 1) / kTileCols, row_blocks = (a.M + kRowsX - 1) / kRowsX;
     if (ntiles > 65535 || row_blocks > 65535) return hipErrorInvalidValue;
     if (lds > 48 * 1024) {  // beyond the default dynamic-LDS allowance
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_dyn_kernel<Act, UB, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_dyn_kernel<Act, UB, D, BOUND>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((tile_dyn_kernel<Act, UB, D>), dim3(a.split, ntiles, row_blocks), dim3(waves * 64), lds, stream, a, finish, sync);
+    hipLaunchKernelGGL((tile_dyn_kernel<Act, UB, D, BOUND>), dim3(a.split, ntiles, row_blocks), dim3(waves * 64), lds, stream, a, finish, sync);
     return hipGetLastError();
+}
+
+template <typename Act, int UB, int D>
+hipError_t launch_ud(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
+{
+    // two units in flight need more than 128 registers: up to eight waves per workgroup only
+    if (D == 2 && waves > 8) return hipErrorInvalidValue;
+    if (D == 2) return launch_udb<Act, UB, D, 512>(a, finish, sync, waves, stream);
+    return launch_udb<Act, UB, D, 1024>(a, finish, sync, waves, stream);
 }
 
 }  // namespace

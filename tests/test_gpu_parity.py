@@ -142,6 +142,31 @@ def test_four_wave_form_exact_sums_and_one_hot_rows(gpu):
         binding.tune("tile_rows", 0)
 
 
+def test_tile_ticket_form_with_two_units_in_flight(gpu):
+    """The M <= 16 TILE form hands its units out by ticket and sums them exactly: two units in flight per wave (knob
+    tile_depth) and other wave counts must give the bits of the scheduler's form, on ragged shapes and group sizes."""
+    _, binding = gpu
+    for (M, K, N, group) in [(5, 1024, 136, 128), (16, 2048, 264, 128), (9, 768, 72, 64), (2, 1024, 520, 32), (13, 4096, 64, 256)]:
+        X, Wp, s, Zp = wl.make(M, K, N, index=2400 + M + K + N, group=group)
+        ref = orc.gemm(X, Wp, s, Zp, group)
+        G = K // group
+        for split in sorted({1, 2, 3, G}):
+            if split > G or split > 63:
+                continue
+            say("ticket form", M, K, N, group, split)
+            base = run_gpu(gpu, X, Wp, s, Zp, group, kernel=binding.KERNEL_TILE, split=split)
+            assert err_ratio(base, ref) <= 1.0
+            for depth, waves in [(2, 0), (2, 4), (1, 12), (2, 12)]:
+                binding.tune("tile_depth", depth)
+                binding.tune("tile_waves", waves)
+                try:
+                    Y = run_gpu(gpu, X, Wp, s, Zp, group, kernel=binding.KERNEL_TILE, split=split)
+                finally:
+                    binding.tune("tile_depth", 0)
+                    binding.tune("tile_waves", 0)
+                assert np.array_equal(Y, base), (M, K, N, group, split, depth, waves)
+
+
 def _tile_rows_cases(gpu, rows_x):
     _, binding = gpu
     for (M, K, N, group) in [(33, 640, 72, 128), (130, 512, 136, 128), (200, 1024, 200, 128), (40, 256, 64, 128),
