@@ -361,10 +361,38 @@ __global__ __launch_bounds__(64 * kWaves) void tile_wide_kernel(const GemmArgs a
 #pragma unroll
             for (int i = 0; i < 4; ++i) mine[(16 * rt + 4 * g4 + i) * (kTileCols / 4) + j] = mine4[rt][i];
     };
-    if (finish == kFinishAccumulator)
+    if (finish == kFinishAccumulator) {
+        // one atomic add per output: consecutive lanes on consecutive outputs (w4a16_finish.h)
         reduce_and_finish<typename Codes::Act, kRowsX, kTileCols, 1, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
-    else
-        reduce_and_finish<typename Codes::Act, kRowsX, kTileCols, 4, 4>(a, finish, sync, smem, write_mine, red_waves, m0, tile * kTileCols, slice);
+        return;
+    }
+    // Y, or FP32 partials: the waves exchange their sums in the layout the registers have.  The 4 kRT (row tile, i)
+    // pieces of a lane are dealt out to the four waves, kRT neighbouring ones each; a wave writes the pieces it does
+    // not own into its own staging space (nobody else ever touched it, and its loads have landed: no barrier before),
+    // and after one barrier adds up its pieces, in the order of the waves whoever the owner is, and stores them.
+    float4_t *const own_space = reinterpret_cast<float4_t *>(smem + (size_t)wave * kWaveBytes);
+#pragma unroll
+    for (int u = 0; u < 4 * kRT; ++u)
+        if (u / kRT != wave) own_space[u * 64 + lane] = mine4[u >> 2][u & 3];
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 4 * kRT; ++u) {
+        if (u / kRT != wave) continue;  // uniform
+        float4_t v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            if (w == wave) v += mine4[u >> 2][u & 3];
+            else v += reinterpret_cast<const float4_t *>(smem + (size_t)w * kWaveBytes)[u * 64 + lane];
+        }
+        const int m = m0 + 16 * (u >> 2) + 4 * g4 + (u & 3), col = tile * kTileCols + 4 * j;
+        if (m >= a.M || col >= a.N) continue;  // N is a multiple of 8: the four columns are inside together
+        const size_t out = (size_t)m * a.N + col;
+        typedef typename Codes::Act Act;
+        if (finish == kFinishDirect)
+            *reinterpret_cast<uint2_t *>(a.Y + out) = (uint2_t){Act::pack2(v[0], v[1]), Act::pack2(v[2], v[3])};
+        else
+            *reinterpret_cast<float4_t *>(a.partials + (size_t)slice * a.M * a.N + out) = v;
+    }
 }
 
 template <int RT>
