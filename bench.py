@@ -123,6 +123,36 @@ def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, wa
         e1.record(stream)
         torch.cuda.synchronize()
         us = us_min = e0.elapsed_time(e1) * 1e3 / steps
+    # Context, never the value: the latency of one call on an idle stream (events around a single eager call), and
+    # what the memory system gives a kernel that only reads the same weights, scales and zero points, no arithmetic.
+    single = []
+    for i in range(15):
+        torch.cuda.synchronize()
+        e0.record(stream)
+        call(warmup + steps + i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        single.append(e0.elapsed_time(e1) * 1e3)
+    probe_us = None
+    if graph:
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        for i in range(min(warmup, 2 * copies)):
+            binding.stream_probe(sets[i % copies], sink)
+        torch.cuda.synchronize()
+        gp = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gp):
+            for i in range(steps):
+                binding.stream_probe(sets[i % copies], sink, stream=torch.cuda.current_stream())
+        gp.replay()
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(3):
+            e0.record(stream)
+            gp.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e3 / steps)
+        probe_us = float(np.median(times))
     nbytes = wl.algorithmic_bytes(M, cfg.K, cfg.N, cfg.group)
     flops = 2.0 * M * cfg.K * cfg.N
     plan = binding.query_plan(M, cfg.N, cfg.K, cfg.group, kernel, split)
@@ -132,6 +162,8 @@ def time_gemm(torch, binding, wl, name, M, steps, warmup, kernel=-1, split=0, wa
         "TFLOPs": flops / us * 1e-6, "mfma_frac": flops / us * 1e-6 / MFMA_FP16_PEAK_TFLOPS,
         "cache": "warm (one weight copy, last-level-cache resident)" if warm else "cold (%d weight copies)" % copies,
         "plan": plan,
+        "single_call_us": float(np.median(single)),
+        "read_only_probe_us": probe_us, "read_only_probe_GBps": (wbytes / probe_us * 1e-3) if probe_us else None,
     }
     return res, Y, (dX, sets[(warmup + steps - 1) % copies])
 
@@ -407,6 +439,9 @@ def main():
                    "plan": res["plan"]},
         "us_per_gemm_min": res["us_per_gemm_min"], "timing": "median of 5 replays of a HIP graph of %d GEMMs (fastest replay beside it)" % args.steps,
         "achieved_TBps": res["GBps"] * 1e-3, "achieved_TFLOPs": res["TFLOPs"],
+        # context, not the metric: one call alone on an idle stream, and a kernel that only reads the same weights
+        "context": {"single_call_us": res["single_call_us"], "read_only_probe_us": res["read_only_probe_us"],
+                    "read_only_probe_TBps": res["read_only_probe_GBps"] * 1e-3 if res["read_only_probe_GBps"] else None},
         # the roofline that bounds the kernel: HBM below the ridge of 2.5 PFLOP/s over 8 TB/s = 312.5 flop/byte, MFMA above
         "roofline": ({"bound": "hbm", "achieved": res["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["hbm_frac"]}
                      if 2.0 * args.M * cfg.K * cfg.N / res["algorithmic_bytes"] < 1e3 * MFMA_FP16_PEAK_TFLOPS / HBM_PEAK_GBS else

@@ -205,6 +205,14 @@ int w4a16_reduce(const float *partials, int S, int M, int N, void *Y, void *stre
 int w4a16_dequant(const uint32_t *Wpacked, const void *scales, const uint32_t *zeros, int group, int N, int K,
                   void *W16, void *stream);
 
+/* Measurement aid, not a step of the method (for benchmarks that want the practical ceiling of the memory system
+ * beside a multiply's time): reads up to three device arrays once (16-byte-aligned pointers; a null pointer skips
+ * that array; trailing bytes beyond a multiple of 16 are not read), one workgroup per compute unit, and keeps
+ * nothing.  `sink`: one 32-bit word of device memory that anchors the loads (written only in the practically
+ * impossible case that everything read cancels to one bit pattern).  Enqueues one kernel on `stream`. */
+int w4a16_stream_probe(const void *a, size_t a_bytes, const void *b, size_t b_bytes, const void *c, size_t c_bytes, void *sink,
+                       void *stream);
+
 /* Offline tool (Section 2.1, Eq. 1: x_q = round(x / s) + z): quantizes FP16 weights W16 [K, N] (row-major, device
  * pointer) into the three tensors w4a16_gemm reads, all owned by the caller and fully overwritten: Wpacked [K/8, N],
  * scales FP16 [K/group, N], zeros [K/group, N/8].  The paper leaves the choice of s and z open; per group of one

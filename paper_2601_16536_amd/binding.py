@@ -18,7 +18,7 @@ KERNEL_AUTO, KERNEL_WAVE_SPLIT, KERNEL_STRIPE, KERNEL_TILE = -1, 0, 3, 4  # 1 an
 EXPORTS = (
     "w4a16_gemm", "w4a16_gemm_ex", "w4a16_gemm_ws", "w4a16_gemm_noalloc", "w4a16_gemm_bf16", "w4a16_set_workspace", "w4a16_tune",
     "w4a16_workspace_bytes", "w4a16_query_plan",
-    "w4a16_reduce", "w4a16_dequant", "w4a16_quantize", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
+    "w4a16_reduce", "w4a16_dequant", "w4a16_quantize", "w4a16_stream_probe", "w4a16_status_string", "w4a16_last_hip_error", "w4a16_shutdown",
 )
 
 
@@ -83,6 +83,7 @@ def lib():
         L.w4a16_reduce.argtypes = [vp, ci, ci, ci, vp, vp]
         L.w4a16_dequant.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp]
         L.w4a16_quantize.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+        L.w4a16_stream_probe.argtypes = [vp, sz, vp, sz, vp, sz, vp, vp]
         L.w4a16_status_string.argtypes = [ci]
         L.w4a16_status_string.restype = ctypes.c_char_p
         L.w4a16_last_hip_error.argtypes = []
@@ -276,6 +277,20 @@ def dequant(Wpacked, scales, zeros, group: int, out=None, stream=None):
     if rc:
         raise W4A16Error(rc, "w4a16_dequant")
     return W16
+
+
+def stream_probe(tensors, sink, stream=None):
+    """Measurement aid: reads up to three device tensors once (what a multiply reads: weights, scales, zero points) and
+    keeps nothing.  `sink`: a device tensor of at least four bytes."""
+    ts = [t for t in tensors if t is not None]
+    if not 1 <= len(ts) <= 3 or not all(t.is_cuda and t.is_contiguous() for t in ts) or not sink.is_cuda:
+        raise TypeError("one to three contiguous device tensors and a device sink wanted")
+    args = []
+    for t in ts + [None] * (3 - len(ts)):
+        args += [t.data_ptr() if t is not None else None, t.numel() * t.element_size() if t is not None else 0]
+    rc = lib().w4a16_stream_probe(*args, sink.data_ptr(), _stream(stream))
+    if rc:
+        raise W4A16Error(rc, "w4a16_stream_probe")
 
 
 def quantize(W16, group: int, stream=None):

@@ -606,6 +606,20 @@ int w4a16_dequant(const uint32_t *Wpacked, const void *scales, const uint32_t *z
     return W4A16_OK;
 }
 
+int w4a16_stream_probe(const void *a, size_t a_bytes, const void *b, size_t b_bytes, const void *c, size_t c_bytes, void *sink,
+                       void *stream)
+{
+    t_hip_error[0] = 0;
+    if (!sink || (!a && !b && !c)) return W4A16_ERR_NULL;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return W4A16_ERR_ALIGN;
+    const int dev = current_device();
+    if (dev < 0) { note_hip_error(hipErrorNoDevice); return W4A16_ERR_HIP; }
+    hipError_t e = launch_stream_probe(a, a ? a_bytes : 0, b, b ? b_bytes : 0, c, c ? c_bytes : 0, static_cast<uint32_t *>(sink),
+                                       compute_units(dev), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) { note_hip_error(e); return W4A16_ERR_HIP; }
+    return W4A16_OK;
+}
+
 int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, void *scales, uint32_t *zeros,
                    void *stream)
 {

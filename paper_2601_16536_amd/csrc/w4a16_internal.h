@@ -26,6 +26,9 @@ struct GemmArgs {
 
 // Multiply launchers: enqueue on `stream`, return the launch status.
 hipError_t launch_wave_split(const GemmArgs &a, int tile_n, hipStream_t stream);
+// Measurement aid: reads up to three arrays once, one workgroup per compute unit (w4a16_probe.hip).
+hipError_t launch_stream_probe(const void *a, size_t na, const void *b, size_t nb, const void *c, size_t nc, uint32_t *sink, int cus,
+                               hipStream_t stream);
 // How the K slices of different workgroups meet (the scheduler's choice per shape).
 enum Finish : int {
     kFinishDirect = 0,       // S = 1: the workgroup casts and stores Y

@@ -485,6 +485,25 @@ def test_reduce_entry_point(gpu):
     assert np.array_equal(Y.cpu().numpy(), acc.astype(np.float16))
 
 
+def test_stream_probe_reads_and_keeps_nothing(gpu):
+    """The measurement aid reads up to three arrays and must leave them and its sink as they were; argument errors come
+    back as codes."""
+    torch, binding = gpu
+    X, Wp, s, Zp = wl.make(1, 2048, 264, index=2500)
+    _, dW, dS, dZ = binding.to_device(X, Wp, s, Zp)
+    before = (dW.clone(), dS.clone(), dZ.clone())
+    sink = torch.full((4,), 12345, dtype=torch.int32, device="cuda")
+    binding.stream_probe((dW, dS, dZ), sink)
+    binding.stream_probe((dW,), sink)
+    torch.cuda.synchronize()
+    assert torch.equal(dW, before[0]) and torch.equal(dS, before[1]) and torch.equal(dZ, before[2])
+    assert sink.tolist() == [12345] * 4
+    L = binding.lib()
+    assert L.w4a16_stream_probe(None, 0, None, 0, None, 0, sink.data_ptr(), None) == binding.ERR_NULL
+    assert L.w4a16_stream_probe(dW.data_ptr(), 64, None, 0, None, 0, None, None) == binding.ERR_NULL
+    assert L.w4a16_stream_probe(dW.data_ptr() + 4, 64, None, 0, None, 0, sink.data_ptr(), None) == binding.ERR_ALIGN
+
+
 def test_dequant_entry_point_bit_exact(gpu):
     """Phase 1 alone: fp16(s (q - z)), one rounding of an exact FP32 product - bit for bit the oracle's
     dequantised weights rounded to FP16 (ragged N, several group sizes, every nibble and zero-point position)."""
