@@ -455,6 +455,8 @@ def main():
                      "algorithmic_bytes_per_launch": res["algorithmic_bytes"],
                      "algorithmic_flops_per_launch": 2.0 * args.M * cfg.K * cfg.N})
     line["cpu_baseline"] = cpu
+    line["environment"] = {"device": torch.cuda.get_device_name(0), "compute_units": torch.cuda.get_device_properties(0).multi_processor_count,
+                           "hip": torch.version.hip, "torch": torch.__version__, "host_cpus": os.cpu_count()}
 
     if args.table:
         rows = []
