@@ -9,7 +9,7 @@
 // just before their MFMAs, 95 vector instructions and 20 MFMAs per block, one kind after the other, and the waves
 // wait a quarter of their time.  With four waves a wave has 512 registers, enough to
 //   - keep the arithmetic exact and still drop the sum of x: the B operand is q - z as an exact FP16 integer
-//     (two vector instructions more per word than the bare code, but no fifth MFMA per four, no 2^-4 scaling of X,
+//     (twelve vector instructions per word instead of five, but no fifth MFMA per four, no 2^-4 scaling of X,
 //     and Eq. 2's step is one FMA per output element and group, s (sum_k x_k (q_k - z)), instead of two);
 //   - put the step of one group between the first MFMAs of the next (tile by tile: step, then the MFMA that restarts
 //     the tile's sums);
