@@ -28,7 +28,8 @@ def test_noalloc_entry_point_matches_gemm():
     # (M, K, N, kernel, split): an accumulator plan of the stripe family, FP32 partials for the second pass, then
     # smaller inputs of both kinds and a direct plan, so that stale contents of the array would show
     T = binding.KERNEL_TILE
-    cases = [(2, 8192, 4104, -1, 0), (130, 768, 2056, T, 3), (1, 4096, 1024, -1, 0), (33, 512, 264, T, 4), (8, 2048, 520, -1, 0),
+    # the first two: 32 rows of X per workgroup (the four-wave TILE form), FP32 partials, then the accumulator
+    cases = [(48, 512, 8192, T, 2), (40, 512, 8192, T, 2), (2, 8192, 4104, -1, 0), (130, 768, 2056, T, 3), (1, 4096, 1024, -1, 0), (33, 512, 264, T, 4), (8, 2048, 520, -1, 0),
              (3, 1024, 264, -1, 0), (5, 256, 72, T, 1)]
     p = lambda t: t.data_ptr()
     st = torch.cuda.current_stream().cuda_stream
