@@ -233,9 +233,12 @@ template <typename Act, int UB, int D>
 hipError_t launch_ud(const GemmArgs &a, int finish, unsigned long long *sync, int waves, hipStream_t stream)
 {
     // two units in flight need more than 128 registers: up to eight waves per workgroup only
-    if (D == 2 && waves > 8) return hipErrorInvalidValue;
-    if (D == 2) return launch_udb<Act, UB, D, 512>(a, finish, sync, waves, stream);
-    return launch_udb<Act, UB, D, 1024>(a, finish, sync, waves, stream);
+    if constexpr (D == 2) {
+        if (waves > 8) return hipErrorInvalidValue;
+        return launch_udb<Act, UB, D, 512>(a, finish, sync, waves, stream);
+    } else {
+        return launch_udb<Act, UB, D, 1024>(a, finish, sync, waves, stream);
+    }
 }
 
 }  // namespace
