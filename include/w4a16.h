@@ -235,6 +235,7 @@ int w4a16_quantize(const void *W16, int group, int N, int K, uint32_t *Wpacked, 
  *   "tile_rows"      rows of X per TILE workgroup (16, 32, 64)
  *   "tile_dyn"       16 rows of X per workgroup: 1 = units of K always handed out by ticket, 2 = never
  *   "tile_depth"     units in flight per wave of that form (1, 2)
+ *   "tile_unit"      blocks of 32 k per unit of that form (1, 2; default: a whole group, at most 4)
  *   "tile_waves"     waves per TILE workgroup (4..8)
  *   "tile_wide"      2: TILE at 32 or 64 rows of X per workgroup, FP16, group 128: the eight-wave form instead of
  *                    the four-wave one

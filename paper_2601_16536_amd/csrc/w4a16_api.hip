@@ -63,6 +63,7 @@ struct Tuning {
     int tile_dyn = 0;       // 16 rows of X per workgroup: 1 = units always handed out by ticket, 2 = never (equal runs per wave)
     int tile_depth = 0;     // units in flight per wave of the ticket form (1, 2)
     int tile_waves = 0;     // waves per TILE workgroup (4..8)
+    int tile_unit = 0;      // 16 rows of X per workgroup, by ticket: blocks of 32 k per unit (1, 2; default: up to 4 within a group)
     int tile_wide = 0;      // TILE at 32 or 64 rows of X per workgroup, FP16, group 128: 2 = the eight-wave form instead of the four-wave one
     int log = 0;            // 1: every call prints its plan on stderr
 };
@@ -75,7 +76,7 @@ const Knob kKnobs[] = {
     {"stripe_finish", &Tuning::stripe_finish}, {"stripe_waves", &Tuning::stripe_waves}, {"stripe_dyn", &Tuning::stripe_dyn},
     {"stripe_unit", &Tuning::stripe_unit},     {"stripe_depth", &Tuning::stripe_depth}, {"stripe_dot2", &Tuning::stripe_dot2},
     {"tile_rows", &Tuning::tile_rows},         {"tile_dyn", &Tuning::tile_dyn},         {"tile_depth", &Tuning::tile_depth},
-    {"tile_waves", &Tuning::tile_waves},       {"tile_wide", &Tuning::tile_wide},
+    {"tile_waves", &Tuning::tile_waves},       {"tile_wide", &Tuning::tile_wide},         {"tile_unit", &Tuning::tile_unit},
     {"log", &Tuning::log},
 };
 
@@ -487,7 +488,7 @@ int run(const char *entry, const void *X, const uint32_t *Wp, const void *scales
     } else if (plan.kernel == W4A16_KERNEL_STRIPE) {
         e = launch_stripe(a, finish, b.sync, plan.waves_k, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE && tile_by_ticket(M, plan.tile_m)) {
-        e = launch_tile_dyn(a, finish, b.sync, plan.waves_k, tuning().tile_depth == 2 && !bf16 && plan.waves_k <= 8 ? 2 : 1, st);
+        e = launch_tile_dyn(a, finish, b.sync, plan.waves_k, tuning().tile_depth == 2 && !bf16 && plan.waves_k <= 8 ? 2 : 1, tuning().tile_unit, st);
     } else if (plan.kernel == W4A16_KERNEL_TILE && tile_wide(plan.tile_m, group) && !bf16) {
         // four waves with the whole register file each; measured on M = 128, K = N = 8192: 27.5 us against 33.1 us with eight
         e = launch_tile_wide(a, finish, b.sync, plan.tile_m, st);

@@ -69,7 +69,7 @@ hipError_t launch_tile(const GemmArgs &a, int finish, unsigned long long *sync, 
 hipError_t launch_tile_wide(const GemmArgs &a, int finish, unsigned long long *sync, int rows_x, hipStream_t stream);
 // TILE family, 16 rows of X per workgroup, the slice handed out to the waves by ticket (w4a16_tile_dyn.hip); `depth` (1, 2)
 // units in flight per wave.
-hipError_t launch_tile_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int depth, hipStream_t stream);
+hipError_t launch_tile_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int depth, int unit_blocks, hipStream_t stream);
 // Clears n words of a fixed-point accumulator.
 hipError_t launch_accumulator_clear(unsigned long long *acc, size_t n, hipStream_t stream);
 // Phase 1 alone (Algorithm 1): W16[K, N] = fp16(s (q - z)) in global memory, for the unfused variant.

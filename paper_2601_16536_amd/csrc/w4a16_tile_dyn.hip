@@ -245,7 +245,7 @@ hipError_t launch_ud(const GemmArgs &a, int finish, unsigned long long *sync, in
 
 // `finish` says how the slices meet (w4a16_finish.h); `sync` is the accumulator it may need.  `depth`: units in
 // flight per wave (1 or 2).
-hipError_t launch_tile_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int depth, hipStream_t stream)
+hipError_t launch_tile_dyn(const GemmArgs &a, int finish, unsigned long long *sync, int waves, int depth, int unit_blocks, hipStream_t stream)
 {
     if (a.group % 32 != 0 || waves < 1 || waves > 16) return hipErrorInvalidValue;
     if (!finish_args_ok(a, finish, sync)) return hipErrorInvalidValue;
@@ -253,7 +253,8 @@ hipError_t launch_tile_dyn(const GemmArgs &a, int finish, unsigned long long *sy
     if (rows * a.N * 4ull >= 0x7F000000ull) return hipErrorInvalidValue;  // slice-relative 32-bit buffer offsets
     if ((unsigned long long)a.M * a.K * 2ull >= 0x7F000000ull) return hipErrorInvalidValue;
     const int bpg = a.group / 32;
-    const int ub = bpg % 4 == 0 ? 4 : (bpg % 2 == 0 ? 2 : 1);  // blocks per unit: a unit never crosses a quantisation group
+    int ub = bpg % 4 == 0 ? 4 : (bpg % 2 == 0 ? 2 : 1);  // blocks per unit: a unit never crosses a quantisation group
+    if ((unit_blocks == 1 || unit_blocks == 2) && unit_blocks < ub) ub = unit_blocks;  // smaller on request (sweeps)
     if (a.bf16) {  // bfloat16 activations: the scheduler's depth only
         if (depth != 1) return hipErrorInvalidValue;
         if (ub == 4) return launch_ud<ActBF16, 4, 1>(a, finish, sync, waves, stream);
