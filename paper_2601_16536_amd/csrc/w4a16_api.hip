@@ -203,6 +203,30 @@ size_t stripe_lds(int M, int group, int gps, int waves)
 }
 size_t stripe_lds_max(int M) { return (size_t)(stripe_by_ticket(M) ? stripe_dyn_lds_limit() : stripe_lds_limit()); }
 
+// Estimated time (us) of a TILE plan for M > 16: `rows` of X per workgroup, K in S slices.  A model of three terms with
+// constants measured on K = N = 8192 and on the paper's Fig. 2 shapes at M = 32 and 64 (it orders the 30 plans measured
+// there as the clock does): a fixed 3 us; rounds of workgroups x blocks of 32 k per wave x the time of a block
+// (four-wave form: 0.24 us at 32 rows, 0.37 at 64; eight-wave form: 0.37, 0.56, 0.94 at 16, 32, 64 rows); and how the
+// slices meet (accumulator: 1 us, and beyond 200 K adds 1 us per 60 K; second pass: 3.3 us and the partials at 3 TB/s).
+double tile_plan_cost(int M, int N, int K, int group, int rows, int S, int cus)
+{
+    const int G = K / group;
+    const int gps = (G + S - 1) / S;
+    S = (G + gps - 1) / gps;
+    const bool four = tile_wide(rows, group);
+    const int waves = four ? 4 : 8;
+    const double per_block = four ? (rows == 64 ? 0.37 : 0.24) : (rows == 64 ? 0.94 : (rows == 32 ? 0.56 : 0.37));
+    const long long tiles = (N + 63) / 64, wgs = tiles * ((M + rows - 1) / rows) * S;
+    const long long rounds = (wgs + cus - 1) / cus;
+    const long long blocks = ((long long)gps * (group / 32) + waves - 1) / waves;
+    double finish = 0.0;
+    if (S > 1) {
+        const double adds = (double)S * M * N;
+        finish = slices_meet_in_accumulator(M, N, S) ? 1.0 + (adds > 2e5 ? (adds - 2e5) / 6e4 : 0.0) : 3.3 + 2.0 * adds * 4.0 / 3e6;
+    }
+    return 3.0 + (double)rounds * (double)blocks * per_block + finish;
+}
+
 int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4a16_plan *p)
 {
     const int G = K / group;
@@ -268,7 +292,24 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         int rows_x = 64;
         while (rows_x > 16 && (rows_x / 2 >= M || tiles * ((M + rows_x - 1) / rows_x) < cus)) rows_x /= 2;
         const int tr = tuning().tile_rows;
-        if (tr == 16 || tr == 32 || tr == 64) rows_x = tr;
+        if (tr == 16 || tr == 32 || tr == 64) {
+            rows_x = tr;
+        } else if (split == 0 && M > 16 && group % 32 == 0) {
+            // M > 16, the scheduler's own S: the rule above is a poor one where it puts a few workgroups more than
+            // compute units into a second round, or gives up large row blocks that a split of K would have filled
+            // (measured, N = 7168, K = 18432, M = 64: 49.7 us at 16 rows against 33.0 at 64 rows, S = 2): the
+            // cheapest of (rows, S) by the model, S up to one workgroup per compute unit
+            double best = 1e30;
+            for (int r = 16; r <= 64; r *= 2) {
+                if (r > 16 && r / 2 >= M) break;  // more than half of the block's rows would be empty
+                const long long w1 = tiles * ((M + r - 1) / r);
+                const int smax = (int)(cus / w1) < 1 ? 1 : ((int)(cus / w1) > G ? G : (int)(cus / w1));
+                for (int s = 1; s <= smax; ++s) {
+                    const double c = tile_plan_cost(M, N, K, group, r, s, cus);
+                    if (c < best) { best = c; rows_x = r; S = s; }
+                }
+            }
+        }
         p->tile_m = rows_x;
         const int tw = tuning().tile_waves;
         if (tw >= 4 && tw <= (tile_by_ticket(M, rows_x) ? 16 : 8)) { p->waves_k = tw; p->threads = 64 * tw; }

@@ -175,6 +175,27 @@ def test_headline_plan_is_one_launch(binding):
     assert p["workgroups"] == 256 and p["groups_per_split"] == 28
 
 
+def test_tile_plans_for_many_rows_follow_the_cost_model(binding):
+    """M > 16: rows of X per workgroup and S come from a small cost model instead of "the largest block that still
+    fills the compute units without a split".  The cases are the ones whose measured order the model was fitted to:
+    N = 7168, K = 18432 and N = 4608, K = 10240 at M = 64 ran 34 % faster at 64 rows with K split than at 16 rows."""
+    q = lambda M, N, K: binding.query_plan(M, N, K, 128)
+    for (M, N, K, rows, S) in [(64, 7168, 18432, 64, 2), (64, 4608, 10240, 64, 3), (64, 4096, 16384, 64, 4), (64, 2048, 10240, 16, 2),
+                               (32, 7168, 18432, 32, 2), (32, 4096, 16384, 16, 2), (32, 8192, 8192, 16, 1), (64, 8192, 8192, 32, 1),
+                               (128, 8192, 8192, 64, 1)]:
+        p = q(M, N, K)
+        assert (p["tile_m"], p["split"]) == (rows, S), (M, N, K, p)
+        assert p["workgroups"] <= 256 or S == 1
+    # a forced split keeps the older rule for the rows; the knob forces the rows and leaves S to the rule
+    assert binding.query_plan(64, 7168, 18432, 128, binding.KERNEL_TILE, 1)["tile_m"] == 16
+    binding.tune("tile_rows", 32)
+    try:
+        p = q(64, 7168, 18432)
+        assert (p["tile_m"], p["split"]) == (32, 1)
+    finally:
+        binding.tune("tile_rows", 0)
+
+
 def test_product_does_not_touch_the_oracle():
     """The product path must not import, link or call anything under oracle/."""
     pkg = os.path.join(ROOT, "paper_2601_16536_amd")
