@@ -294,17 +294,17 @@ int make_plan(int M, int N, int K, int group, int kernel, int split, int cus, w4
         const int tr = tuning().tile_rows;
         if (tr == 16 || tr == 32 || tr == 64) {
             rows_x = tr;
-        } else if (split == 0 && M > 16 && group % 32 == 0) {
+        } else if (M > 16 && group % 32 == 0) {
             // M > 16, the scheduler's own S: the rule above is a poor one where it puts a few workgroups more than
             // compute units into a second round, or gives up large row blocks that a split of K would have filled
             // (measured, N = 7168, K = 18432, M = 64: 49.7 us at 16 rows against 33.0 at 64 rows, S = 2): the
-            // cheapest of (rows, S) by the model, S up to one workgroup per compute unit
+            // cheapest of (rows, S) by the model, S up to one workgroup per compute unit (a forced S: the rows for it)
             double best = 1e30;
             for (int r = 16; r <= 64; r *= 2) {
                 if (r > 16 && r / 2 >= M) break;  // more than half of the block's rows would be empty
                 const long long w1 = tiles * ((M + r - 1) / r);
-                const int smax = (int)(cus / w1) < 1 ? 1 : ((int)(cus / w1) > G ? G : (int)(cus / w1));
-                for (int s = 1; s <= smax; ++s) {
+                const int smax = split ? split : ((int)(cus / w1) < 1 ? 1 : ((int)(cus / w1) > G ? G : (int)(cus / w1)));
+                for (int s = split ? split : 1; s <= smax; ++s) {
                     const double c = tile_plan_cost(M, N, K, group, r, s, cus);
                     if (c < best) { best = c; rows_x = r; S = s; }
                 }

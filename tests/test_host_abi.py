@@ -186,8 +186,9 @@ def test_tile_plans_for_many_rows_follow_the_cost_model(binding):
         p = q(M, N, K)
         assert (p["tile_m"], p["split"]) == (rows, S), (M, N, K, p)
         assert p["workgroups"] <= 256 or S == 1
-    # a forced split keeps the older rule for the rows; the knob forces the rows and leaves S to the rule
-    assert binding.query_plan(64, 7168, 18432, 128, binding.KERNEL_TILE, 1)["tile_m"] == 16
+    # a forced split gets the rows the model finds cheapest for it; the knob forces the rows and leaves S to the rule
+    assert binding.query_plan(64, 7168, 18432, 128, binding.KERNEL_TILE, 1)["tile_m"] == 32
+    assert binding.query_plan(64, 7168, 18432, 128, binding.KERNEL_TILE, 2)["tile_m"] == 64
     binding.tune("tile_rows", 32)
     try:
         p = q(64, 7168, 18432)
